@@ -1,0 +1,314 @@
+/*
+ * muw_oracle.c -- plain CPU fp64 oracle for micro-structured weight unification / pruning.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may include, link or call this file:
+ * only the test-suite, the smoke check and the benchmark's "cpu_baseline" leg use it.  It shares no
+ * code, header, table or helper with the HIP library; every formula below is written out from the
+ * paper's definitions so it can be checked against them by eye.
+ *
+ * Notation (paper, Sec. 3.1): a layer's weight tensor W is partitioned into micro-blocks; block j
+ * holds the weights w_{j,l}, l = 0..B-1.  Here a block is B consecutive weights along the
+ * contraction (K) direction inside one output row n -- the paper's [B,1] block shape (Table 1).
+ * A block is left DENSE, UNIFIED (every weight becomes +q or -q, Eq. 2, with q the mean absolute
+ * value of the block) or PRUNED (q = 0: the block is removed from storage and compute).
+ *
+ * Readings of points the paper leaves open (each is listed in the design document as well):
+ *  - which blocks are pruned: the n_p blocks with the smallest squared L2 norm e_p = sum w^2,
+ *    because the Q-step of Sec. 3.3 (Eq. 6) is a Euclidean projection; ties go to the lower index.
+ *  - which blocks are unified: among the blocks that are not pruned, the n_u blocks with the
+ *    smallest unification distortion e_u = sum (|w| - q)^2 (the same Euclidean argument).
+ *  - pruning is decided first, unification second.
+ *  - sign rule: literally Eq. 2 -- w >= 0 maps to +q, so -0.0 maps to +q as well.
+ *  - the stored magnitude is q rounded ONCE (round-to-nearest-even) from fp64 to the storage type.
+ *
+ * Parity pins (tests/test_oracle_pins.py): brute-force projection on tiny blocks, brute-force
+ * subset selection, Table 1 reductions, the Fig. 1 parameter counts, the ResNet-50 MAC estimates of
+ * Sec. 4.5, closed-form Gaussian statistics, dense/all-pruned special cases of the GEMM, im2col and
+ * library convolution for the conv.  No function in this file is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_TAG_DENSE 0
+#define ORACLE_TAG_UNIFIED 1
+#define ORACLE_TAG_PRUNED 2
+
+#define ORACLE_STORE_F32 0
+#define ORACLE_STORE_BF16 1
+
+/* Block counts from ratios: n = floor(r * NB + 1/2) in IEEE double arithmetic, pruning first, the
+ * unified count clipped to what is left.  (Sec. 4.3: one ratio per layer, applied to that layer's
+ * blocks.)  Returns 0, or -1 for ratios outside [0,1]. */
+int oracle_counts(int64_t NB, double r_unify, double r_prune, int64_t *n_u, int64_t *n_p)
+{
+    if (!(r_unify >= 0.0 && r_unify <= 1.0) || !(r_prune >= 0.0 && r_prune <= 1.0) || NB < 0)
+        return -1;
+    int64_t np = (int64_t)floor(r_prune * (double)NB + 0.5);
+    int64_t nu = (int64_t)floor(r_unify * (double)NB + 0.5);
+    if (np > NB) np = NB;
+    if (nu > NB - np) nu = NB - np;
+    *n_u = nu;
+    *n_p = np;
+    return 0;
+}
+
+/* Convolution weights arrive as [Cout][Cin][KH][KW]; the GEMM the convolution is lowered to
+ * (Sec. 3.2) has N = Cout rows and K = KH*KW*Cin columns with k = (kh*KW + kw)*Cin + cin, so that a
+ * block of B consecutive k is a run of B input channels at one filter tap of one output channel. */
+void oracle_conv_weight_gemm_view(const double *W_oihw, int64_t Cout, int64_t Cin, int64_t KH,
+                                  int64_t KW, double *Wg)
+{
+    for (int64_t co = 0; co < Cout; ++co)
+        for (int64_t ci = 0; ci < Cin; ++ci)
+            for (int64_t kh = 0; kh < KH; ++kh)
+                for (int64_t kw = 0; kw < KW; ++kw) {
+                    int64_t k = (kh * KW + kw) * Cin + ci;
+                    Wg[co * (KH * KW * Cin) + k] = W_oihw[((co * Cin + ci) * KH + kh) * KW + kw];
+                }
+}
+
+/* Inverse of the view above, for handing the projected weights to a direct convolution. */
+void oracle_gemm_view_to_conv_weight(const double *Wg, int64_t Cout, int64_t Cin, int64_t KH,
+                                     int64_t KW, double *W_oihw)
+{
+    for (int64_t co = 0; co < Cout; ++co)
+        for (int64_t ci = 0; ci < Cin; ++ci)
+            for (int64_t kh = 0; kh < KH; ++kh)
+                for (int64_t kw = 0; kw < KW; ++kw) {
+                    int64_t k = (kh * KW + kw) * Cin + ci;
+                    W_oihw[((co * Cin + ci) * KH + kh) * KW + kw] = Wg[co * (KH * KW * Cin) + k];
+                }
+}
+
+/* One round-to-nearest-even rounding of a finite non-negative double to the storage format,
+ * returned as a double.  bf16: 8 significant bits, fp32 exponent range (smallest subnormal 2^-133).
+ * fp32: the C conversion, which is round-to-nearest-even under the default rounding mode. */
+double oracle_round_to_storage(double q, int storage)
+{
+    if (storage == ORACLE_STORE_F32) return (double)(float)q;
+    if (q == 0.0 || !isfinite(q)) return q;
+    int e;
+    (void)frexp(fabs(q), &e);               /* |q| = m * 2^e with 0.5 <= m < 1 */
+    int quantum_exp = e - 8;                /* 8 significant bits: spacing 2^(e-8) */
+    if (quantum_exp < -133) quantum_exp = -133;
+    double scaled = ldexp(fabs(q), -quantum_exp);
+    double r = rint(scaled);                /* ties to even (default rounding mode) */
+    double out = ldexp(r, quantum_exp);
+    if (out > 3.3895313892515355e38) out = INFINITY; /* above the largest finite bf16 */
+    return q < 0.0 ? -out : out;
+}
+
+/* Per-block scores (Sec. 3.1 for q; Sec. 3.3, Eq. 6 for the two distances).  Left-to-right sums,
+ * separate multiply and add, all in double:
+ *   s1  = sum |w_l|          q = s1 / B
+ *   e_p = sum w_l * w_l                      (squared distance to the all-zero block)
+ *   e_u = sum (|w_l| - q) * (|w_l| - q)      (squared distance to the unified block, Eq. 2)
+ * Returns 0, or -2 if any weight is not finite. */
+int oracle_block_scores(const double *Wg, int64_t N, int64_t K, int64_t B, double *q_out,
+                        double *e_p_out, double *e_u_out)
+{
+    int64_t KB = K / B;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t kb = 0; kb < KB; ++kb) {
+            const double *w = Wg + n * K + kb * B;
+            double s1 = 0.0, e_p = 0.0, e_u = 0.0;
+            for (int64_t l = 0; l < B; ++l) {
+                if (!isfinite(w[l])) return -2;
+                s1 = s1 + fabs(w[l]);
+            }
+            double q = s1 / (double)B;
+            for (int64_t l = 0; l < B; ++l) {
+                double sq = w[l] * w[l];
+                e_p = e_p + sq;
+            }
+            for (int64_t l = 0; l < B; ++l) {
+                double d = fabs(w[l]) - q;
+                double dd = d * d;
+                e_u = e_u + dd;
+            }
+            int64_t j = n * KB + kb;
+            q_out[j] = q;
+            e_p_out[j] = e_p;
+            e_u_out[j] = e_u;
+        }
+    return 0;
+}
+
+typedef struct {
+    double key;
+    int64_t idx;
+} oracle_keyed;
+
+static int oracle_keyed_cmp(const void *a, const void *b)
+{
+    const oracle_keyed *x = (const oracle_keyed *)a, *y = (const oracle_keyed *)b;
+    if (x->key < y->key) return -1;
+    if (x->key > y->key) return 1;
+    if (x->idx < y->idx) return -1;
+    if (x->idx > y->idx) return 1;
+    return 0;
+}
+
+/* Unify(): the projection of a layer onto "n_p pruned blocks, n_u unified blocks, the rest dense".
+ *   Wg     [N][K] weights exactly as stored (widened to double), GEMM view
+ *   tags   [NB]  ORACLE_TAG_*               NB = N*K/B, block index j = n*(K/B) + kb
+ *   signs  [NB]  bit l set iff w_l < 0 (unified blocks only, else 0)
+ *   mags   [NB]  stored magnitude q^ as a double (unified blocks only, else 0)
+ *   What   [N][K] projected weights: +-q^ in unified blocks, 0 in pruned blocks, w elsewhere
+ * Returns 0; -1 bad arguments; -2 non-finite weight. */
+int oracle_encode(const double *Wg, int64_t N, int64_t K, int64_t B, int64_t n_u, int64_t n_p,
+                  int storage, uint8_t *tags, uint16_t *signs, double *mags, double *What)
+{
+    if (N <= 0 || K <= 0 || B <= 0 || B > 16 || K % B != 0) return -1;
+    int64_t KB = K / B, NB = N * KB;
+    if (n_p < 0 || n_u < 0 || n_p + n_u > NB) return -1;
+
+    double *q = (double *)malloc(sizeof(double) * (size_t)NB);
+    double *e_p = (double *)malloc(sizeof(double) * (size_t)NB);
+    double *e_u = (double *)malloc(sizeof(double) * (size_t)NB);
+    oracle_keyed *order = (oracle_keyed *)malloc(sizeof(oracle_keyed) * (size_t)NB);
+    int rc = oracle_block_scores(Wg, N, K, B, q, e_p, e_u);
+    if (rc != 0) goto done;
+
+    for (int64_t j = 0; j < NB; ++j) tags[j] = ORACLE_TAG_DENSE;
+
+    /* pruned: the n_p smallest (e_p, index) */
+    for (int64_t j = 0; j < NB; ++j) {
+        order[j].key = e_p[j];
+        order[j].idx = j;
+    }
+    qsort(order, (size_t)NB, sizeof(oracle_keyed), oracle_keyed_cmp);
+    for (int64_t r = 0; r < n_p; ++r) tags[order[r].idx] = ORACLE_TAG_PRUNED;
+
+    /* unified: among the others, the n_u smallest (e_u, index) */
+    int64_t rest = 0;
+    for (int64_t j = 0; j < NB; ++j)
+        if (tags[j] != ORACLE_TAG_PRUNED) {
+            order[rest].key = e_u[j];
+            order[rest].idx = j;
+            ++rest;
+        }
+    qsort(order, (size_t)rest, sizeof(oracle_keyed), oracle_keyed_cmp);
+    for (int64_t r = 0; r < n_u; ++r) tags[order[r].idx] = ORACLE_TAG_UNIFIED;
+
+    /* values */
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t kb = 0; kb < KB; ++kb) {
+            int64_t j = n * KB + kb;
+            const double *w = Wg + n * K + kb * B;
+            double *v = What + n * K + kb * B;
+            signs[j] = 0;
+            mags[j] = 0.0;
+            if (tags[j] == ORACLE_TAG_PRUNED) {
+                for (int64_t l = 0; l < B; ++l) v[l] = 0.0;
+            } else if (tags[j] == ORACLE_TAG_UNIFIED) {
+                double qh = oracle_round_to_storage(q[j], storage);
+                mags[j] = qh;
+                for (int64_t l = 0; l < B; ++l) {
+                    if (w[l] >= 0.0) {
+                        v[l] = qh;
+                    } else {
+                        v[l] = -qh;
+                        signs[j] |= (uint16_t)(1u << l);
+                    }
+                }
+            } else {
+                for (int64_t l = 0; l < B; ++l) v[l] = w[l];
+            }
+        }
+done:
+    free(q);
+    free(e_p);
+    free(e_u);
+    free(order);
+    return rc;
+}
+
+/* Y[m][n] = sum_k X[m][k] * What[n][k]  (Sec. 3.2: the layer as a GEMM), k ascending, in double.
+ * Rows are independent; they are spread over the host cores only to bound the run time. */
+void oracle_gemm(const double *X, int64_t M, int64_t K, const double *What, int64_t N, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) acc += X[m * K + k] * What[n * K + k];
+            Y[m * N + n] = acc;
+        }
+}
+
+/* The same GEMM for callers that hold the stored 32-bit values: widened to double on the fly so the
+ * benchmark's CPU leg does not need three fp64 copies of a large layer. */
+void oracle_gemm_f32in(const float *X, int64_t M, int64_t K, const float *What, int64_t N, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) acc += (double)X[m * K + k] * (double)What[n * K + k];
+            Y[m * N + n] = acc;
+        }
+}
+
+/* Direct convolution with the projected weights (Sec. 3.2), cross-correlation, zero padding:
+ *   Y[b][co][oh][ow] = sum_{kh,kw,ci} X[b][ci][oh*s + kh - p][ow*s + kw - p] * What[co][(kh*KW+kw)*Cin+ci]
+ *   OH = (H + 2p - KH)/s + 1,  OW = (W + 2p - KW)/s + 1.
+ * X is [Nb][Cin][H][W], What is the GEMM view [Cout][KH*KW*Cin], Y is [Nb][Cout][OH][OW]. */
+void oracle_conv2d(const double *X, int64_t Nb, int64_t Cin, int64_t H, int64_t W, const double *What,
+                   int64_t Cout, int64_t KH, int64_t KW, int64_t stride, int64_t pad, double *Y)
+{
+    int64_t OH = (H + 2 * pad - KH) / stride + 1;
+    int64_t OW = (W + 2 * pad - KW) / stride + 1;
+    int64_t K = KH * KW * Cin;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < Nb; ++b)
+        for (int64_t co = 0; co < Cout; ++co)
+            for (int64_t oh = 0; oh < OH; ++oh)
+                for (int64_t ow = 0; ow < OW; ++ow) {
+                    double acc = 0.0;
+                    for (int64_t kh = 0; kh < KH; ++kh)
+                        for (int64_t kw = 0; kw < KW; ++kw)
+                            for (int64_t ci = 0; ci < Cin; ++ci) {
+                                int64_t ih = oh * stride + kh - pad;
+                                int64_t iw = ow * stride + kw - pad;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                                acc += X[((b * Cin + ci) * H + ih) * W + iw] *
+                                       What[co * K + (kh * KW + kw) * Cin + ci];
+                            }
+                    Y[((b * Cout + co) * OH + oh) * OW + ow] = acc;
+                }
+}
+
+/* Storage / multiplier counters of the encoded layer (Table 1; Fig. 1; Sec. 4.5).
+ *   params : weights that must be stored, sign bits not counted (the table's convention):
+ *            one per unified block, B per dense block, none per pruned block
+ *   mults  : multiplications per activation row: a unified block needs one (sum the signed
+ *            activations, multiply once by q), a dense block B, a pruned block none
+ *   bits   : exact size of the format: a 2-bit tag per block, value_bits + B per unified block,
+ *            value_bits * B per dense block */
+void oracle_counters(int64_t NB, int64_t B, int64_t n_u, int64_t n_p, int64_t value_bits,
+                     int64_t *params, int64_t *mults, int64_t *bits)
+{
+    int64_t n_d = NB - n_u - n_p;
+    *params = n_u + B * n_d;
+    *mults = n_u + B * n_d;
+    *bits = 2 * NB + n_u * (value_bits + B) + n_d * value_bits * B;
+}
+
+int oracle_omp_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,161 @@
+"""ctypes front-end of the C oracle (oracle/muw_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+`cpu_baseline` leg.  All arithmetic lives in the C file; this module only marshals numpy arrays.
+Arrays of stored weights/activations are passed as float64 holding the stored values exactly.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+TAG_DENSE, TAG_UNIFIED, TAG_PRUNED = 0, 1, 2
+STORE_F32, STORE_BF16 = 0, 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = C.CDLL(path)
+        i64, dbl, p = C.c_int64, C.c_double, C.c_void_p
+        L.oracle_counts.argtypes = [i64, dbl, dbl, C.POINTER(i64), C.POINTER(i64)]
+        L.oracle_counts.restype = C.c_int
+        L.oracle_conv_weight_gemm_view.argtypes = [p, i64, i64, i64, i64, p]
+        L.oracle_conv_weight_gemm_view.restype = None
+        L.oracle_gemm_view_to_conv_weight.argtypes = [p, i64, i64, i64, i64, p]
+        L.oracle_gemm_view_to_conv_weight.restype = None
+        L.oracle_round_to_storage.argtypes = [dbl, C.c_int]
+        L.oracle_round_to_storage.restype = dbl
+        L.oracle_block_scores.argtypes = [p, i64, i64, i64, p, p, p]
+        L.oracle_block_scores.restype = C.c_int
+        L.oracle_encode.argtypes = [p, i64, i64, i64, i64, i64, C.c_int, p, p, p, p]
+        L.oracle_encode.restype = C.c_int
+        L.oracle_gemm.argtypes = [p, i64, i64, p, i64, p]
+        L.oracle_gemm.restype = None
+        L.oracle_gemm_f32in.argtypes = [p, i64, i64, p, i64, p]
+        L.oracle_gemm_f32in.restype = None
+        L.oracle_conv2d.argtypes = [p, i64, i64, i64, i64, p, i64, i64, i64, i64, i64, p]
+        L.oracle_conv2d.restype = None
+        L.oracle_counters.argtypes = [i64, i64, i64, i64, i64, C.POINTER(i64), C.POINTER(i64),
+                                      C.POINTER(i64)]
+        L.oracle_counters.restype = None
+        L.oracle_omp_threads.argtypes = []
+        L.oracle_omp_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def counts(NB, r_unify, r_prune):
+    nu, np_ = C.c_int64(), C.c_int64()
+    rc = lib().oracle_counts(int(NB), float(r_unify), float(r_prune), C.byref(nu), C.byref(np_))
+    if rc != 0:
+        raise ValueError("ratios must lie in [0, 1]")
+    return nu.value, np_.value
+
+
+def conv_weight_gemm_view(W_oihw):
+    W = _f64(W_oihw)
+    Cout, Cin, KH, KW = W.shape
+    out = np.empty((Cout, KH * KW * Cin), dtype=np.float64)
+    lib().oracle_conv_weight_gemm_view(_ptr(W), Cout, Cin, KH, KW, _ptr(out))
+    return out
+
+
+def gemm_view_to_conv_weight(Wg, Cin, KH, KW):
+    Wg = _f64(Wg)
+    Cout = Wg.shape[0]
+    out = np.empty((Cout, Cin, KH, KW), dtype=np.float64)
+    lib().oracle_gemm_view_to_conv_weight(_ptr(Wg), Cout, Cin, KH, KW, _ptr(out))
+    return out
+
+
+def round_to_storage(q, storage):
+    return lib().oracle_round_to_storage(float(q), int(storage))
+
+
+def block_scores(Wg, B):
+    Wg = _f64(Wg)
+    N, K = Wg.shape
+    NB = N * K // B
+    q, e_p, e_u = (np.empty(NB, dtype=np.float64) for _ in range(3))
+    rc = lib().oracle_block_scores(_ptr(Wg), N, K, B, _ptr(q), _ptr(e_p), _ptr(e_u))
+    if rc != 0:
+        raise ValueError("non-finite weight")
+    return q, e_p, e_u
+
+
+def encode(Wg, B, n_u, n_p, storage):
+    """Returns (tags u8[NB], signs u16[NB], mags f64[NB], What f64[N,K])."""
+    Wg = _f64(Wg)
+    N, K = Wg.shape
+    if B <= 0 or K % B:
+        raise ValueError("K must be a multiple of B")
+    NB = N * K // B
+    tags = np.empty(NB, dtype=np.uint8)
+    signs = np.empty(NB, dtype=np.uint16)
+    mags = np.empty(NB, dtype=np.float64)
+    What = np.empty((N, K), dtype=np.float64)
+    rc = lib().oracle_encode(_ptr(Wg), N, K, B, int(n_u), int(n_p), int(storage), _ptr(tags),
+                             _ptr(signs), _ptr(mags), _ptr(What))
+    if rc == -2:
+        raise ValueError("non-finite weight")
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return tags, signs, mags, What
+
+
+def gemm(X, What):
+    X, What = _f64(X), _f64(What)
+    M, K = X.shape
+    N = What.shape[0]
+    assert What.shape[1] == K
+    Y = np.empty((M, N), dtype=np.float64)
+    lib().oracle_gemm(_ptr(X), M, K, _ptr(What), N, _ptr(Y))
+    return Y
+
+
+def gemm_f32in(X32, What32):
+    X = np.ascontiguousarray(X32, dtype=np.float32)
+    W = np.ascontiguousarray(What32, dtype=np.float32)
+    M, K = X.shape
+    N = W.shape[0]
+    assert W.shape[1] == K
+    Y = np.empty((M, N), dtype=np.float64)
+    lib().oracle_gemm_f32in(_ptr(X), M, K, _ptr(W), N, _ptr(Y))
+    return Y
+
+
+def conv2d(X, What_gemm_view, KH, KW, stride, pad):
+    X, Wg = _f64(X), _f64(What_gemm_view)
+    Nb, Cin, H, W = X.shape
+    Cout = Wg.shape[0]
+    assert Wg.shape[1] == KH * KW * Cin
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    Y = np.empty((Nb, Cout, OH, OW), dtype=np.float64)
+    lib().oracle_conv2d(_ptr(X), Nb, Cin, H, W, _ptr(Wg), Cout, KH, KW, stride, pad, _ptr(Y))
+    return Y
+
+
+def counters(NB, B, n_u, n_p, value_bits=16):
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    lib().oracle_counters(int(NB), int(B), int(n_u), int(n_p), int(value_bits), C.byref(a),
+                          C.byref(b), C.byref(c))
+    return a.value, b.value, c.value
+
+
+def omp_threads():
+    return lib().oracle_omp_threads()

@@ -1,0 +1,241 @@
+"""Seeded synthetic inputs and the workload table.
+
+This module serves both the HIP path and the CPU oracle's callers and therefore holds NONE of the
+method's arithmetic: only a counter-based random generator, dtype bit conversions and the shapes of
+the benchmark workloads.  It needs numpy only (no torch, no HIP library).
+
+Generator: value i of stream (seed, stream) comes from two SplitMix64-finalised counters turned into
+uniforms and a Box-Muller transform in float64, scaled by `std`, then rounded ONCE to the storage
+type on the host.  The same host array feeds the oracle (widened exactly to float64) and is uploaded
+to the GPU, so neither side depends on a library's random stream.
+
+The paper evaluates trained VGG-16 / ResNet-50 / MobileNet-V2 / autoencoder / ConvNet models on
+ImageNet, CIFAR-100 and DCASE2017; neither the data nor trained weights are available here, and the
+kernels' cost depends only on shapes and on the tag statistics.  These inputs are stand-ins with the
+layer shapes of those networks (ResNet-50 bottleneck geometry, transformer projection sizes) and
+i.i.d. Gaussian values.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_CHUNK = 1 << 22
+
+
+def _mix64(z):
+    """SplitMix64 output function on a uint64 array (wrapping arithmetic)."""
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def _stream_key(seed, stream):
+    with np.errstate(over="ignore"):
+        k = _mix64(np.array([np.uint64(seed) * _GOLDEN + np.uint64(stream) + np.uint64(1)],
+                            dtype=np.uint64))
+    return k[0]
+
+
+def standard_normal(seed, n, stream=0):
+    """n float64 N(0,1) values; value i depends only on (seed, stream, i)."""
+    out = np.empty(n, dtype=np.float64)
+    key = _stream_key(seed, stream)
+    with np.errstate(over="ignore"):
+        for lo in range(0, n, _CHUNK):
+            hi = min(n, lo + _CHUNK)
+            ctr = np.arange(lo, hi, dtype=np.uint64)
+            a = _mix64(key + (np.uint64(2) * ctr + np.uint64(1)) * _GOLDEN)
+            b = _mix64(key + (np.uint64(2) * ctr + np.uint64(2)) * _GOLDEN)
+            u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+            u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+            out[lo:hi] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    return out
+
+
+# ---- dtype helpers (bit conversions only) -------------------------------------------------------
+
+def f32_to_bf16_bits(x32):
+    """Round float32 to bfloat16 (nearest even); returns the uint16 bit patterns."""
+    b = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32)
+    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits):
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(
+        np.float32)
+
+
+def bf16_bits_to_f64(bits):
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+@dataclass
+class Tensor:
+    """A host tensor in its storage dtype.  `dtype` is "f32" or "bf16"; `data` is float32 or the
+    uint16 bf16 bit patterns; `f64()` widens the stored values exactly."""
+    dtype: str
+    data: np.ndarray
+
+    @property
+    def shape(self):
+        return self.data.shape
+
+    def f64(self):
+        if self.dtype == "f32":
+            return self.data.astype(np.float64)
+        return bf16_bits_to_f64(self.data).reshape(self.data.shape)
+
+    def f32(self):
+        if self.dtype == "f32":
+            return self.data
+        return bf16_bits_to_f32(self.data).reshape(self.data.shape)
+
+
+def normal_tensor(seed, shape, std, dtype, stream=0):
+    n = int(np.prod(shape))
+    v = (standard_normal(seed, n, stream) * std).astype(np.float32)
+    if dtype == "f32":
+        return Tensor("f32", v.reshape(shape))
+    if dtype == "bf16":
+        return Tensor("bf16", f32_to_bf16_bits(v).reshape(shape))
+    raise ValueError(dtype)
+
+
+def from_values(values, dtype):
+    """Wrap given values (rounded once to the storage dtype); for hand-made test cases."""
+    v = np.asarray(values, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return Tensor("f32", v)
+    return Tensor("bf16", f32_to_bf16_bits(v).reshape(v.shape))
+
+
+# ---- workload table --------------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class LinearCase:
+    name: str
+    M: int
+    N: int
+    K: int
+    B: int
+    r_unify: float
+    r_prune: float
+    dtype: str
+    w_std: float
+    seed: int
+
+
+@dataclass(frozen=True)
+class ConvCase:
+    name: str
+    batch: int
+    Cin: int
+    H: int
+    W: int
+    Cout: int
+    KH: int
+    KW: int
+    stride: int
+    pad: int
+    B: int
+    r_unify: float
+    r_prune: float
+    dtype: str
+    seed: int
+    repeat: int = 1          # how many layers of the network share this shape
+
+    @property
+    def OH(self):
+        return (self.H + 2 * self.pad - self.KH) // self.stride + 1
+
+    @property
+    def OW(self):
+        return (self.W + 2 * self.pad - self.KW) // self.stride + 1
+
+    @property
+    def M(self):
+        return self.batch * self.OH * self.OW
+
+    @property
+    def N(self):
+        return self.Cout
+
+    @property
+    def K(self):
+        return self.KH * self.KW * self.Cin
+
+    @property
+    def w_std(self):
+        # "Kaiming normal": fan-in mode with the ReLU gain, std = sqrt(2 / (Cin*KH*KW))
+        return float(np.sqrt(2.0 / (self.Cin * self.KH * self.KW)))
+
+
+def config1():
+    return LinearCase("cfg1_linear_fp32", 64, 256, 256, 4, 0.5, 0.25, "f32", 0.05, 0)
+
+
+def config2(batch=32):
+    return ConvCase("cfg2_conv3x3_64", batch, 64, 56, 56, 64, 3, 3, 1, 1, 4, 0.6, 0.3, "bf16", 2000)
+
+
+def config4(M):
+    return LinearCase(f"cfg4_proj4096_M{M}", M, 4096, 4096, 16, 0.7, 0.25, "bf16", 0.02, 4000)
+
+
+def config5(M, which):
+    N, K = (11008, 4096) if which == "up" else (4096, 11008)
+    return LinearCase(f"cfg5_mlp_{which}_M{M}", M, N, K, 8, 0.4, 0.5, "bf16", 0.02,
+                      5000 + (0 if which == "up" else 1))
+
+
+def resnet50_conv_shapes():
+    """(Cin, H, Cout, ksize, stride, repeat) of the 52 encoded convolutions of a ResNet-50-shaped
+    network at 224x224 input (bottleneck 1x1 / 3x3 / 1x1, stride on the 3x3, 1x1 projection
+    shortcuts).  The 7x7 stem (Cin = 3, not divisible by the block length) is excluded, as the
+    paper excludes the first layer."""
+    shapes = []
+    cin, res = 64, 56
+    for stage, (mid, blocks) in enumerate([(64, 3), (128, 4), (256, 6), (512, 3)]):
+        out = mid * 4
+        for b in range(blocks):
+            stride = 2 if (b == 0 and stage > 0) else 1
+            shapes.append((cin, res, mid, 1, 1))              # 1x1 reduce
+            shapes.append((mid, res, mid, 3, stride))         # 3x3 (strided in the first block)
+            res_out = res // stride
+            shapes.append((mid, res_out, out, 1, 1))          # 1x1 expand
+            if b == 0:
+                shapes.append((cin, res, out, 1, stride))     # projection shortcut
+            cin, res = out, res_out
+    merged = {}
+    for s in shapes:
+        merged[s] = merged.get(s, 0) + 1
+    return [(*s, r) for s, r in merged.items()]
+
+
+def config3(batch=64):
+    cases = []
+    for i, (cin, res, cout, ks, stride, rep) in enumerate(resnet50_conv_shapes()):
+        cases.append(ConvCase(f"cfg3_{ks}x{ks}s{stride}_{cin}to{cout}_at{res}", batch, cin, res, res,
+                              cout, ks, ks, stride, ks // 2, 8, 0.5, 0.4, "bf16", 3000 + 2 * i, rep))
+    return cases
+
+
+def make_linear(case, M=None):
+    """Returns (X Tensor [M,K], W Tensor [N,K]) for a LinearCase."""
+    M = case.M if M is None else M
+    X = normal_tensor(case.seed, (M, case.K), 1.0, case.dtype, stream=0)
+    W = normal_tensor(case.seed, (case.N, case.K), case.w_std, case.dtype, stream=1)
+    return X, W
+
+
+def make_conv(case, batch=None):
+    """Returns (X Tensor [Nb,Cin,H,W], W Tensor [Cout,Cin,KH,KW]) for a ConvCase."""
+    nb = case.batch if batch is None else batch
+    X = normal_tensor(case.seed, (nb, case.Cin, case.H, case.W), 1.0, case.dtype, stream=0)
+    W = normal_tensor(case.seed, (case.Cout, case.Cin, case.KH, case.KW), case.w_std, case.dtype,
+                      stream=1)
+    return X, W
