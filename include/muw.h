@@ -1,0 +1,143 @@
+/*
+ * muw.h -- C ABI of the micro-structured unified/pruned-weight GEMM library for AMD MI355X (gfx950).
+ *
+ * The method (paper, Sec. 3.1-3.2): a layer's weights W[N][K] (a fully-connected layer, or a
+ * convolution lowered to a GEMM) are cut into micro-blocks of B consecutive weights along the
+ * contraction direction K inside one output row -- the paper's [B,1] block shape (Table 1).  Every
+ * block is tagged
+ *     PRUNED   all weights zero; nothing is stored and nothing is computed        (Sec. 3.1)
+ *     UNIFIED  every weight is +q or -q with one magnitude q per block; B sign bits and q are stored
+ *              (Eq. 2; q = mean absolute value of the block)
+ *     DENSE    the B weights are kept as they are
+ * and the layer's forward pass Y = X * W^T is computed straight from that format (Sec. 3.2).
+ *
+ * Conventions
+ *  - All "_dev" pointers are DEVICE pointers (HBM of the current HIP device); everything else is a
+ *    HOST pointer.  The library allocates no device memory: every buffer is caller-owned, and
+ *    workspaces are sized by the *_workspace_bytes / *_sizes queries.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  muw_gemm,
+ *    muw_gemm_grouped, muw_conv2d, muw_export and muw_decode only enqueue work; muw_encode enqueues
+ *    and then waits for the stream (it has to read a device flag).
+ *  - Errors: arguments are checked on the host before anything is launched and reported through the
+ *    return value; nothing aborts or throws.  HIP launch failures map to MUW_EHIP.
+ *  - Block index: j = n * (K / B) + kb, block (n, kb) holds W[n][kb*B .. kb*B + B - 1].
+ *  - Supported: B in {4, 8, 16}; storage (magnitudes and dense blocks) bf16 or fp32; activations of
+ *    the same type as the storage; outputs fp32 or bf16.
+ *  - The encoded blob is position independent (offsets only) and may be copied or saved byte for byte.
+ */
+#ifndef MUW_H
+#define MUW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MUW_OK = 0,
+    MUW_EINVAL = 1,       /* null pointer, ratio outside [0,1], negative size, misaligned buffer */
+    MUW_ESHAPE = 2,       /* K % B != 0, Cin % B != 0, KH*KW*Cin != K, ld < row length, ... */
+    MUW_ENOSPC = 3,       /* a caller buffer (blob, workspace) is smaller than the size query says */
+    MUW_ENONFINITE = 4,   /* muw_encode met a NaN or an infinity among the weights */
+    MUW_EUNSUPPORTED = 5, /* block length or dtype combination not implemented */
+    MUW_EHIP = 6          /* a HIP runtime call failed */
+} muw_status;
+
+typedef enum { MUW_F32 = 0, MUW_BF16 = 1 } muw_dtype;
+typedef enum { MUW_TAG_DENSE = 0, MUW_TAG_UNIFIED = 1, MUW_TAG_PRUNED = 2 } muw_tag;
+typedef enum {
+    MUW_LAYOUT_NK = 0,  /* W[N][K], row-major */
+    MUW_LAYOUT_OIHW = 1 /* W[Cout][Cin][KH][KW]; GEMM view N = Cout, k = (kh*KW + kw)*Cin + cin */
+} muw_layout;
+
+/* Plain-old-data description of one encoded layer; caller-owned, lives on the HOST.
+ * The caller fills N, K, B, KH, KW, Cin, wdtype; muw_encode fills n_unified and n_pruned. */
+typedef struct {
+    int64_t N, K;         /* GEMM view of the layer: Y[M][N] = X[M][K] * W[N][K]^T */
+    int32_t B;            /* block length along K; K % B == 0 (convolution: Cin % B == 0) */
+    int32_t KH, KW, Cin;  /* 1, 1, K for a linear layer; K == KH*KW*Cin */
+    int32_t wdtype;       /* muw_dtype of the weights, of the stored magnitudes and dense blocks */
+    int32_t reserved;     /* set to 0 */
+    int64_t n_unified;    /* number of UNIFIED blocks (written by muw_encode) */
+    int64_t n_pruned;     /* number of PRUNED blocks  (written by muw_encode) */
+} muw_desc;
+
+int muw_version(void);
+const char *muw_status_str(muw_status s);
+
+/* Block counts from ratios (Sec. 4.3: one ratio per layer): n_p = floor(r_prune*NB + 1/2),
+ * n_u = min(floor(r_unify*NB + 1/2), NB - n_p), in IEEE double arithmetic.  Host only. */
+muw_status muw_counts(int64_t NB, double r_unify, double r_prune, int64_t *n_u, int64_t *n_p);
+
+/* Upper bound of the blob size and the exact workspace size muw_encode needs for this layer at these
+ * ratios.  Host only. */
+muw_status muw_encode_sizes(const muw_desc *desc, double r_unify, double r_prune, size_t *blob_bytes,
+                            size_t *workspace_bytes);
+
+/* Unify() of Sec. 3.1 / Alg. 1 as a one-shot projection (Sec. 4.3), followed by packing:
+ *   1. per block, in fp64 with separately rounded multiplies and adds, left to right:
+ *        q = (sum |w_l|) / B,  e_p = sum w_l^2,  e_u = sum (|w_l| - q)^2
+ *   2. the n_p blocks with the smallest (e_p, j) become PRUNED (Euclidean projection, Sec. 3.3);
+ *   3. of the others, the n_u blocks with the smallest (e_u, j) become UNIFIED; the rest stay DENSE;
+ *   4. a UNIFIED block stores sign bit l = (w_l < 0) (Eq. 2: w >= 0, including -0.0, maps to +q) and
+ *      q rounded once, to nearest even, from fp64 to the storage type.
+ * W_dev: the weights in `layout`, dtype desc->wdtype, 16-byte aligned.  blob_dev (16-byte aligned,
+ * blob_bytes >= the size query) receives the encoded layer; ws_dev is scratch.  Waits for the
+ * stream before returning.  Returns MUW_ENONFINITE (blob contents undefined) on NaN/Inf weights. */
+muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, double r_unify,
+                      double r_prune, void *blob_dev, size_t blob_bytes, void *ws_dev,
+                      size_t ws_bytes, void *hip_stream);
+
+/* Layout-independent view of an encoded layer, for bit-exact comparison: tags_dev[NB] (muw_tag),
+ * signs_dev[NB] (bit l = w_l < 0; 0 unless UNIFIED), mags_dev[NB] (stored magnitude in wdtype; 0 unless
+ * UNIFIED).  Any of the three may be NULL. */
+muw_status muw_export(const muw_desc *desc, const void *blob_dev, uint8_t *tags_dev,
+                      uint16_t *signs_dev, void *mags_dev, void *hip_stream);
+
+/* The projected weights W^[N][K] (GEMM view, row-major, dtype wdtype): +-q^ in UNIFIED blocks, 0 in
+ * PRUNED blocks, the original weights in DENSE blocks. */
+muw_status muw_decode(const muw_desc *desc, const void *blob_dev, void *What_dev, void *hip_stream);
+
+/* Algorithmic size of the format in bytes: 2 bits per block, (value bits + B) per UNIFIED block,
+ * value bits * B per DENSE block (Table 1's storage count plus the sign and tag bits).  Host only;
+ * uses desc->n_unified / n_pruned. */
+size_t muw_compressed_bytes(const muw_desc *desc);
+
+/* Workspace muw_gemm needs for M activation rows (may be 0).  Host only. */
+size_t muw_gemm_workspace_bytes(const muw_desc *desc, int64_t M);
+
+/* Y[M][N] = X[M][K] * W^^T (Sec. 3.2): PRUNED blocks contribute nothing, UNIFIED blocks contribute
+ * q^ times the signed sum of their activations, DENSE blocks their B products; fp32 accumulation.
+ * X_dev: row-major, row stride ldx elements (ldx >= K), dtype xdtype == desc->wdtype.
+ * Y_dev: row-major, row stride ldy elements (ldy >= N), dtype ydtype (fp32 or bf16).
+ * M == 0 is a no-op. */
+muw_status muw_gemm(const muw_desc *desc, const void *blob_dev, const void *X_dev, muw_dtype xdtype,
+                    int64_t M, int64_t ldx, void *Y_dev, muw_dtype ydtype, int64_t ldy, void *ws_dev,
+                    size_t ws_bytes, void *hip_stream);
+
+/* G independent layers of one shape in a single launch (the many projection GEMMs of one decoding
+ * step): for g < G, Y_g[M][N] = X_g[M][K] * W^_g^T.  blobs_dev, X_ptrs_dev, Y_ptrs_dev are DEVICE
+ * arrays of G device pointers; all layers share desc's N, K, B and dtype (their block counts may
+ * differ); X_g and Y_g are dense row-major (ldx = K, ldy = N).  M <= 16. */
+muw_status muw_gemm_grouped(const muw_desc *desc, int32_t G, const void *const *blobs_dev,
+                            const void *const *X_ptrs_dev, muw_dtype xdtype, int64_t M,
+                            void *const *Y_ptrs_dev, muw_dtype ydtype, void *hip_stream);
+
+/* Workspace muw_conv2d needs (may be 0).  Host only. */
+size_t muw_conv2d_workspace_bytes(const muw_desc *desc, int64_t Nb, int64_t H, int64_t W,
+                                  int32_t stride, int32_t pad);
+
+/* Convolution as an implicit GEMM (Sec. 3.2) over a layer encoded with MUW_LAYOUT_OIHW:
+ *   Y[b][co][oh][ow] = sum_{kh,kw,ci} X[b][ci][oh*stride + kh - pad][ow*stride + kw - pad] * W^[co][ci][kh][kw]
+ * cross-correlation, zero padding, groups = 1, dilation = 1, stride >= 1, pad >= 0.
+ * X_dev: NCHW [Nb][Cin][H][W] dense; Y_dev: NCHW [Nb][Cout][OH][OW] dense, OH = (H + 2 pad - KH)/stride + 1. */
+muw_status muw_conv2d(const muw_desc *desc, const void *blob_dev, const void *X_dev, muw_dtype xdtype,
+                      int64_t Nb, int64_t H, int64_t W, int32_t stride, int32_t pad, void *Y_dev,
+                      muw_dtype ydtype, void *ws_dev, size_t ws_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUW_H */

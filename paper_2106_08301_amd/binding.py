@@ -1,0 +1,229 @@
+"""Thin ctypes binding of libmuw.so (include/muw.h): argument marshalling only.
+
+Every step of the path runs inside the HIP library; PyTorch is used for device memory
+(`torch.empty(..., device="cuda")`) and for the current stream.  If the library has not been built
+the import of this module fails loudly -- there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmuw.so")
+
+MUW_OK, MUW_EINVAL, MUW_ESHAPE, MUW_ENOSPC, MUW_ENONFINITE, MUW_EUNSUPPORTED, MUW_EHIP = range(7)
+MUW_F32, MUW_BF16 = 0, 1
+MUW_TAG_DENSE, MUW_TAG_UNIFIED, MUW_TAG_PRUNED = 0, 1, 2
+MUW_LAYOUT_NK, MUW_LAYOUT_OIHW = 0, 1
+
+EXPORTED = ["muw_version", "muw_status_str", "muw_counts", "muw_encode_sizes", "muw_encode", "muw_export",
+            "muw_decode", "muw_compressed_bytes", "muw_gemm_workspace_bytes", "muw_gemm",
+            "muw_gemm_grouped", "muw_conv2d_workspace_bytes", "muw_conv2d"]
+
+
+class muw_desc(C.Structure):
+    _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("B", C.c_int32), ("KH", C.c_int32),
+                ("KW", C.c_int32), ("Cin", C.c_int32), ("wdtype", C.c_int32), ("reserved", C.c_int32),
+                ("n_unified", C.c_int64), ("n_pruned", C.c_int64)]
+
+
+class MuwError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} (status {status})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2106_08301_amd.build` "
+                          "(the HIP library is the only implementation; there is no fallback)")
+    L = C.CDLL(LIB_PATH)
+    i32, i64, dbl, vp, sz = C.c_int32, C.c_int64, C.c_double, C.c_void_p, C.c_size_t
+    dp = C.POINTER(muw_desc)
+    L.muw_version.restype = C.c_int
+    L.muw_status_str.argtypes = [C.c_int]
+    L.muw_status_str.restype = C.c_char_p
+    L.muw_counts.argtypes = [i64, dbl, dbl, C.POINTER(i64), C.POINTER(i64)]
+    L.muw_encode_sizes.argtypes = [dp, dbl, dbl, C.POINTER(sz), C.POINTER(sz)]
+    L.muw_encode.argtypes = [dp, vp, C.c_int, dbl, dbl, vp, sz, vp, sz, vp]
+    L.muw_export.argtypes = [dp, vp, vp, vp, vp, vp]
+    L.muw_decode.argtypes = [dp, vp, vp, vp]
+    L.muw_compressed_bytes.argtypes = [dp]
+    L.muw_compressed_bytes.restype = sz
+    L.muw_gemm_workspace_bytes.argtypes = [dp, i64]
+    L.muw_gemm_workspace_bytes.restype = sz
+    L.muw_gemm.argtypes = [dp, vp, vp, C.c_int, i64, i64, vp, C.c_int, i64, vp, sz, vp]
+    L.muw_gemm_grouped.argtypes = [dp, i32, vp, vp, C.c_int, i64, vp, C.c_int, vp]
+    L.muw_conv2d_workspace_bytes.argtypes = [dp, i64, i64, i64, i32, i32]
+    L.muw_conv2d_workspace_bytes.restype = sz
+    L.muw_conv2d.argtypes = [dp, vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, C.c_int, vp, sz, vp]
+    for name in ("muw_counts", "muw_encode_sizes", "muw_encode", "muw_export", "muw_decode", "muw_gemm",
+                 "muw_gemm_grouped", "muw_conv2d"):
+        getattr(L, name).restype = C.c_int
+    return L
+
+
+lib = _load()
+
+
+def status_str(status):
+    return lib.muw_status_str(int(status)).decode()
+
+
+def _check(status, where):
+    if status != MUW_OK:
+        raise MuwError(status, where)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return MUW_F32
+    if t.dtype == torch.bfloat16:
+        return MUW_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+_TORCH_DTYPE = {MUW_F32: torch.float32, MUW_BF16: torch.bfloat16}
+
+
+def muw_version():
+    return lib.muw_version()
+
+
+def muw_counts(NB, r_unify, r_prune):
+    nu, np_ = C.c_int64(), C.c_int64()
+    _check(lib.muw_counts(NB, r_unify, r_prune, C.byref(nu), C.byref(np_)), "muw_counts")
+    return nu.value, np_.value
+
+
+def make_desc(N, K, B, wdtype, KH=1, KW=1, Cin=None):
+    return muw_desc(N=N, K=K, B=B, KH=KH, KW=KW, Cin=K if Cin is None else Cin, wdtype=wdtype, reserved=0,
+                    n_unified=0, n_pruned=0)
+
+
+def muw_encode_sizes(desc, r_unify, r_prune):
+    blob, ws = C.c_size_t(), C.c_size_t()
+    _check(lib.muw_encode_sizes(C.byref(desc), r_unify, r_prune, C.byref(blob), C.byref(ws)),
+           "muw_encode_sizes")
+    return blob.value, ws.value
+
+
+class EncodedLayer:
+    """A descriptor plus the device blob it describes (both caller-owned; this is only a holder)."""
+
+    def __init__(self, desc, blob):
+        self.desc, self.blob = desc, blob
+
+    @property
+    def NB(self):
+        return self.desc.N * (self.desc.K // self.desc.B)
+
+    @property
+    def compressed_bytes(self):
+        return lib.muw_compressed_bytes(C.byref(self.desc))
+
+
+def muw_encode(W, B, r_unify, r_prune):
+    """W: cuda tensor [N, K] (linear) or [Cout, Cin, KH, KW] (convolution), fp32 or bf16, contiguous."""
+    assert W.is_cuda and W.is_contiguous()
+    if W.dim() == 2:
+        N, K = W.shape
+        desc, layout = make_desc(N, K, B, _dtype_code(W)), MUW_LAYOUT_NK
+    elif W.dim() == 4:
+        Cout, Cin, KH, KW = W.shape
+        desc = make_desc(Cout, Cin * KH * KW, B, _dtype_code(W), KH, KW, Cin)
+        layout = MUW_LAYOUT_OIHW
+    else:
+        raise ValueError("W must be 2-D or 4-D")
+    blob_bytes, ws_bytes = muw_encode_sizes(desc, r_unify, r_prune)
+    blob = torch.empty(blob_bytes, dtype=torch.uint8, device=W.device)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib.muw_encode(C.byref(desc), _ptr(W), layout, r_unify, r_prune, _ptr(blob), blob_bytes,
+                          _ptr(ws), ws_bytes, _stream()), "muw_encode")
+    return EncodedLayer(desc, blob)
+
+
+def muw_export(layer):
+    """Returns (tags u8[NB], signs int16[NB] (bit pattern of the u16), mags [NB] in the storage dtype)."""
+    dev = layer.blob.device
+    NB = layer.NB
+    tags = torch.empty(NB, dtype=torch.uint8, device=dev)
+    signs = torch.empty(NB, dtype=torch.int16, device=dev)
+    mags = torch.empty(NB, dtype=_TORCH_DTYPE[layer.desc.wdtype], device=dev)
+    _check(lib.muw_export(C.byref(layer.desc), _ptr(layer.blob), _ptr(tags), _ptr(signs), _ptr(mags),
+                          _stream()), "muw_export")
+    return tags, signs, mags
+
+
+def muw_decode(layer):
+    d = layer.desc
+    What = torch.empty((d.N, d.K), dtype=_TORCH_DTYPE[d.wdtype], device=layer.blob.device)
+    _check(lib.muw_decode(C.byref(d), _ptr(layer.blob), _ptr(What), _stream()), "muw_decode")
+    return What
+
+
+def muw_gemm(layer, X, out_dtype=torch.float32, out=None):
+    """Y[M, N] = X[M, K] @ W^.T ; X may be a row-strided view (stride(1) == 1)."""
+    assert X.is_cuda and X.dim() == 2 and (X.shape[0] == 0 or X.stride(1) == 1)
+    d = layer.desc
+    M = X.shape[0]
+    if X.shape[1] != d.K:
+        raise MuwError(MUW_ESHAPE, "muw_gemm")
+    Y = torch.empty((M, d.N), dtype=out_dtype, device=X.device) if out is None else out
+    ws_bytes = lib.muw_gemm_workspace_bytes(C.byref(d), M)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=X.device) if ws_bytes else None
+    ldx = X.stride(0) if M > 1 else d.K
+    _check(lib.muw_gemm(C.byref(d), _ptr(layer.blob), _ptr(X), _dtype_code(X), M, ldx, _ptr(Y),
+                        _dtype_code(Y), Y.stride(0) if M > 0 else d.N, _ptr(ws), ws_bytes, _stream()),
+           "muw_gemm")
+    return Y
+
+
+class GemmGroup:
+    """Device pointer tables for muw_gemm_grouped (built once; the launch itself allocates nothing)."""
+
+    def __init__(self, layers, Xs, out_dtype=torch.float32):
+        d = layers[0].desc
+        self.desc, self.layers, self.Xs = d, layers, Xs
+        self.M = Xs[0].shape[0]
+        dev = Xs[0].device
+        for l, x in zip(layers, Xs):
+            assert (l.desc.N, l.desc.K, l.desc.B, l.desc.wdtype) == (d.N, d.K, d.B, d.wdtype)
+            assert x.shape == (self.M, d.K) and x.is_contiguous()
+        self.Ys = [torch.empty((self.M, d.N), dtype=out_dtype, device=dev) for _ in layers]
+        tab = lambda ts: torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=dev)
+        self.blob_tab, self.x_tab, self.y_tab = tab([l.blob for l in layers]), tab(Xs), tab(self.Ys)
+        self.xdtype, self.ydtype = _dtype_code(Xs[0]), _dtype_code(self.Ys[0])
+
+
+def muw_gemm_grouped(group):
+    _check(lib.muw_gemm_grouped(C.byref(group.desc), len(group.layers), _ptr(group.blob_tab),
+                                _ptr(group.x_tab), group.xdtype, group.M, _ptr(group.y_tab), group.ydtype,
+                                _stream()), "muw_gemm_grouped")
+    return group.Ys
+
+
+def muw_conv2d(layer, X, stride, pad, out_dtype=torch.float32, out=None):
+    """X: NCHW cuda tensor; returns NCHW [Nb, Cout, OH, OW]."""
+    assert X.is_cuda and X.dim() == 4 and X.is_contiguous()
+    d = layer.desc
+    Nb, Cin, H, W = X.shape
+    if Cin != d.Cin:
+        raise MuwError(MUW_ESHAPE, "muw_conv2d")
+    OH = (H + 2 * pad - d.KH) // stride + 1
+    OW = (W + 2 * pad - d.KW) // stride + 1
+    Y = torch.empty((Nb, d.N, OH, OW), dtype=out_dtype, device=X.device) if out is None else out
+    ws_bytes = lib.muw_conv2d_workspace_bytes(C.byref(d), Nb, H, W, stride, pad)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=X.device) if ws_bytes else None
+    _check(lib.muw_conv2d(C.byref(d), _ptr(layer.blob), _ptr(X), _dtype_code(X), Nb, H, W, stride, pad,
+                          _ptr(Y), _dtype_code(Y), _ptr(ws), ws_bytes, _stream()), "muw_conv2d")
+    return Y

@@ -1,0 +1,240 @@
+// muw_api.hip -- the extern "C" boundary declared in include/muw.h: argument checks and dispatch.
+// No device memory is allocated here or anywhere else in the library.
+#include <math.h>
+
+#include "muw_internal.hpp"
+
+using namespace muw;
+
+namespace {
+
+bool supported_block(int32_t B) { return B == 4 || B == 8 || B == 16; }
+bool valid_dtype(int t) { return t == MUW_F32 || t == MUW_BF16; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape rules shared by every entry point that takes a descriptor.
+muw_status check_desc(const muw_desc *d)
+{
+    if (!d) return MUW_EINVAL;
+    if (d->N <= 0 || d->K <= 0 || d->B <= 0 || d->KH <= 0 || d->KW <= 0 || d->Cin <= 0) return MUW_EINVAL;
+    if (!valid_dtype(d->wdtype)) return MUW_EINVAL;
+    if (d->K % d->B != 0 || d->Cin % d->B != 0) return MUW_ESHAPE;
+    if (int64_t(d->KH) * d->KW * d->Cin != d->K) return MUW_ESHAPE;
+    if (!supported_block(d->B)) return MUW_EUNSUPPORTED;
+    if (d->N > (int64_t(1) << 31) || d->K > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    return MUW_OK;
+}
+
+Layout layout_of(const muw_desc *d) { return make_layout(d->N, d->K, d->B, value_bytes(d->wdtype)); }
+
+size_t blob_upper_bound(const Layout &L, int64_t n_u, int64_t n_d)
+{
+    uint64_t b = L.streams_off;
+    b += uint64_t(L.NS) * uint64_t(L.KP) * 2u * uint64_t(L.S) * 8u;  // masks
+    b += uint64_t(n_d) * uint64_t(L.B) * uint64_t(L.vb);             // dense payload
+    b += uint64_t(n_u) * uint64_t(L.vb);                             // magnitudes
+    b += (uint64_t(n_u) * uint64_t(L.B) + 7) / 8;                    // sign bits
+    b += uint64_t(L.NT) * 17u;                                       // per-tile rounding and padding
+    return size_t(align16(b));
+}
+
+}  // namespace
+
+extern "C" {
+
+int muw_version(void) { return 1; }
+
+const char *muw_status_str(muw_status s)
+{
+    switch (s) {
+    case MUW_OK: return "ok";
+    case MUW_EINVAL: return "invalid argument";
+    case MUW_ESHAPE: return "shape mismatch";
+    case MUW_ENOSPC: return "caller buffer too small";
+    case MUW_ENONFINITE: return "non-finite weight";
+    case MUW_EUNSUPPORTED: return "unsupported block length or dtype";
+    case MUW_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+muw_status muw_counts(int64_t NB, double r_unify, double r_prune, int64_t *n_u, int64_t *n_p)
+{
+    if (!n_u || !n_p || NB < 0) return MUW_EINVAL;
+    if (!(r_unify >= 0.0 && r_unify <= 1.0) || !(r_prune >= 0.0 && r_prune <= 1.0)) return MUW_EINVAL;
+    int64_t np = int64_t(floor(r_prune * double(NB) + 0.5));
+    int64_t nu = int64_t(floor(r_unify * double(NB) + 0.5));
+    if (np > NB) np = NB;
+    if (nu > NB - np) nu = NB - np;
+    *n_u = nu;
+    *n_p = np;
+    return MUW_OK;
+}
+
+muw_status muw_encode_sizes(const muw_desc *desc, double r_unify, double r_prune, size_t *blob_bytes,
+                            size_t *workspace_bytes)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (!blob_bytes || !workspace_bytes) return MUW_EINVAL;
+    const Layout L = layout_of(desc);
+    const int64_t NB = L.N * L.KB;
+    int64_t n_u, n_p;
+    rc = muw_counts(NB, r_unify, r_prune, &n_u, &n_p);
+    if (rc != MUW_OK) return rc;
+    *blob_bytes = blob_upper_bound(L, n_u, NB - n_u - n_p);
+    *workspace_bytes = size_t(encode_workspace(L).total);
+    return MUW_OK;
+}
+
+muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, double r_unify,
+                      double r_prune, void *blob_dev, size_t blob_bytes, void *ws_dev, size_t ws_bytes,
+                      void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (!W_dev || !blob_dev || !ws_dev) return MUW_EINVAL;
+    if (layout != MUW_LAYOUT_NK && layout != MUW_LAYOUT_OIHW) return MUW_EINVAL;
+    if (!aligned16(W_dev) || !aligned16(blob_dev) || !aligned16(ws_dev)) return MUW_EINVAL;
+    size_t need_blob, need_ws;
+    rc = muw_encode_sizes(desc, r_unify, r_prune, &need_blob, &need_ws);
+    if (rc != MUW_OK) return rc;
+    if (blob_bytes < need_blob || ws_bytes < need_ws) return MUW_ENOSPC;
+    const Layout L = layout_of(desc);
+    int64_t n_u, n_p;
+    muw_counts(L.N * L.KB, r_unify, r_prune, &n_u, &n_p);
+    bool nonfinite = false;
+    rc = launch_encode(*desc, L, W_dev, int(layout), n_u, n_p, blob_dev, need_blob, ws_dev,
+                       static_cast<hipStream_t>(hip_stream), &nonfinite);
+    if (rc != MUW_OK) return rc;
+    if (nonfinite) return MUW_ENONFINITE;
+    desc->n_unified = n_u;
+    desc->n_pruned = n_p;
+    return MUW_OK;
+}
+
+muw_status muw_export(const muw_desc *desc, const void *blob_dev, uint8_t *tags_dev, uint16_t *signs_dev,
+                      void *mags_dev, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (!blob_dev) return MUW_EINVAL;
+    return launch_export(*desc, layout_of(desc), blob_dev, tags_dev, signs_dev, mags_dev,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+muw_status muw_decode(const muw_desc *desc, const void *blob_dev, void *What_dev, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (!blob_dev || !What_dev) return MUW_EINVAL;
+    return launch_decode(*desc, layout_of(desc), blob_dev, What_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t muw_compressed_bytes(const muw_desc *desc)
+{
+    if (check_desc(desc) != MUW_OK) return 0;
+    const uint64_t NB = uint64_t(desc->N) * uint64_t(desc->K / desc->B);
+    const uint64_t n_u = uint64_t(desc->n_unified), n_p = uint64_t(desc->n_pruned);
+    if (n_u + n_p > NB) return 0;
+    const uint64_t n_d = NB - n_u - n_p, vbits = 8u * uint64_t(value_bytes(desc->wdtype));
+    const uint64_t bits = 2 * NB + n_u * (vbits + uint64_t(desc->B)) + n_d * vbits * uint64_t(desc->B);
+    return size_t((bits + 7) / 8);
+}
+
+size_t muw_gemm_workspace_bytes(const muw_desc *desc, int64_t M)
+{
+    if (check_desc(desc) != MUW_OK || M < 0) return 0;
+    return gemm_workspace_bytes(*desc, layout_of(desc), M);
+}
+
+muw_status muw_gemm(const muw_desc *desc, const void *blob_dev, const void *X_dev, muw_dtype xdtype,
+                    int64_t M, int64_t ldx, void *Y_dev, muw_dtype ydtype, int64_t ldy, void *ws_dev,
+                    size_t ws_bytes, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (M < 0 || !valid_dtype(xdtype) || !valid_dtype(ydtype)) return MUW_EINVAL;
+    if (M == 0) return MUW_OK;
+    if (!blob_dev || !X_dev || !Y_dev) return MUW_EINVAL;
+    if (int(xdtype) != desc->wdtype) return MUW_EUNSUPPORTED;
+    if (ldx < desc->K || ldy < desc->N) return MUW_ESHAPE;
+    if (M > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    const Layout L = layout_of(desc);
+    const size_t need = gemm_workspace_bytes(*desc, L, M);
+    if (need && (!ws_dev || ws_bytes < need)) return MUW_ENOSPC;
+    GemmArgs a{};
+    a.blob = blob_dev;
+    a.X = X_dev;
+    a.Y = Y_dev;
+    a.G = 1;
+    a.M = M;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.ydtype = int(ydtype);
+    return launch_gemm(*desc, L, a, ws_dev, ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+muw_status muw_gemm_grouped(const muw_desc *desc, int32_t G, const void *const *blobs_dev,
+                            const void *const *X_ptrs_dev, muw_dtype xdtype, int64_t M,
+                            void *const *Y_ptrs_dev, muw_dtype ydtype, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (G < 0 || M < 0 || !valid_dtype(xdtype) || !valid_dtype(ydtype)) return MUW_EINVAL;
+    if (G == 0 || M == 0) return MUW_OK;
+    if (!blobs_dev || !X_ptrs_dev || !Y_ptrs_dev) return MUW_EINVAL;
+    if (int(xdtype) != desc->wdtype) return MUW_EUNSUPPORTED;
+    if (M > 16 || G > 65535) return MUW_EUNSUPPORTED;
+    const Layout L = layout_of(desc);
+    GemmArgs a{};
+    a.blobs = blobs_dev;
+    a.Xs = X_ptrs_dev;
+    a.Ys = Y_ptrs_dev;
+    a.G = G;
+    a.M = M;
+    a.ldx = desc->K;
+    a.ldy = desc->N;
+    a.ydtype = int(ydtype);
+    return launch_gemm(*desc, L, a, nullptr, 0, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t muw_conv2d_workspace_bytes(const muw_desc *desc, int64_t Nb, int64_t H, int64_t W, int32_t stride,
+                                  int32_t pad)
+{
+    if (check_desc(desc) != MUW_OK || Nb < 0 || H <= 0 || W <= 0 || stride < 1 || pad < 0) return 0;
+    return conv2d_workspace_bytes(*desc, layout_of(desc), Nb, H, W, stride, pad);
+}
+
+muw_status muw_conv2d(const muw_desc *desc, const void *blob_dev, const void *X_dev, muw_dtype xdtype,
+                      int64_t Nb, int64_t H, int64_t W, int32_t stride, int32_t pad, void *Y_dev,
+                      muw_dtype ydtype, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (Nb < 0 || H <= 0 || W <= 0 || stride < 1 || pad < 0) return MUW_EINVAL;
+    if (!valid_dtype(xdtype) || !valid_dtype(ydtype)) return MUW_EINVAL;
+    if (H + 2 * int64_t(pad) < desc->KH || W + 2 * int64_t(pad) < desc->KW) return MUW_ESHAPE;
+    if (Nb == 0) return MUW_OK;
+    if (!blob_dev || !X_dev || !Y_dev) return MUW_EINVAL;
+    if (int(xdtype) != desc->wdtype) return MUW_EUNSUPPORTED;
+    const Layout L = layout_of(desc);
+    ConvArgs a{};
+    a.blob = blob_dev;
+    a.X = X_dev;
+    a.Y = Y_dev;
+    a.Nb = Nb;
+    a.H = H;
+    a.W = W;
+    a.OH = (H + 2 * int64_t(pad) - desc->KH) / stride + 1;
+    a.OW = (W + 2 * int64_t(pad) - desc->KW) / stride + 1;
+    a.stride = stride;
+    a.pad = pad;
+    a.ydtype = int(ydtype);
+    if (a.Nb * a.OH * a.OW > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    const size_t need = conv2d_workspace_bytes(*desc, L, Nb, H, W, stride, pad);
+    if (need && (!ws_dev || ws_bytes < need)) return MUW_ENOSPC;
+    return launch_conv2d(*desc, L, a, ws_dev, ws_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

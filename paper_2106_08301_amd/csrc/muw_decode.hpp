@@ -1,0 +1,80 @@
+// muw_decode.hpp -- per-lane decode of one panel of an encoded layer (device code, private).
+//
+// A wavefront walks the panels of a tile in order, carrying the running payload counts (ru, rd).
+// decode_panel_* returns the executing lane's 16 weights of the panel (row r = lane % 16,
+// k = 16 (lane / 16) .. + 15 inside the panel): PRUNED blocks give zeros without touching any
+// payload (Sec. 3.1), UNIFIED blocks give +-q^ (Eq. 2), DENSE blocks their stored values.
+// `tile` may point to global memory or to a copy of the tile stream in LDS.
+#pragma once
+#include "muw_layout.hpp"
+
+namespace muw {
+
+// bf16: 8 dwords, dword d = weights (2d, 2d+1); dwords 0..3 are MFMA h = 0, dwords 4..7 are h = 1.
+template <int B>
+__device__ inline void decode_panel_bf16(const uint8_t *tile, const TileStreams &ts, int panel,
+                                         uint32_t &ru, uint32_t &rd, int lane, uint32_t *out)
+{
+    constexpr int S = 16 / B;
+    const uint64_t *masks = reinterpret_cast<const uint64_t *>(tile) + panel * 2 * S;
+    const uint16_t *mags = reinterpret_cast<const uint16_t *>(tile + ts.mag_off);
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        const uint64_t mu = masks[j], md = masks[S + j];
+        const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
+        ru += __popcll(mu);
+        rd += __popcll(md);
+        uint32_t q = 0, s = 0;
+        if ((mu >> lane) & 1) {
+            q = mags[rku];
+            s = load_sign_field<B>(tile + ts.sign_off, rku);
+        }
+        decode_block_bf16<B>(q, s, out + j * (B / 2));
+        if ((md >> lane) & 1) {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(tile + ts.dense_off) + rkd * (B / 2);
+#pragma unroll
+            for (int d = 0; d < B / 2; ++d) out[j * (B / 2) + d] = src[d];
+        }
+    }
+}
+
+// fp32: 16 floats in k order.
+template <int B>
+__device__ inline void decode_panel_f32(const uint8_t *tile, const TileStreams &ts, int panel,
+                                        uint32_t &ru, uint32_t &rd, int lane, float *out)
+{
+    constexpr int S = 16 / B;
+    const uint64_t *masks = reinterpret_cast<const uint64_t *>(tile) + panel * 2 * S;
+    const uint32_t *mags = reinterpret_cast<const uint32_t *>(tile + ts.mag_off);
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        const uint64_t mu = masks[j], md = masks[S + j];
+        const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
+        ru += __popcll(mu);
+        rd += __popcll(md);
+        uint32_t q = 0, s = 0;
+        if ((mu >> lane) & 1) {
+            q = mags[rku];
+            s = load_sign_field<B>(tile + ts.sign_off, rku);
+        }
+#pragma unroll
+        for (int l = 0; l < B; ++l)
+            out[j * B + l] = __uint_as_float(q ^ (((s >> sign_pos(B, l)) & 1u) << 31));
+        if ((md >> lane) & 1) {
+            const float *src = reinterpret_cast<const float *>(tile + ts.dense_off) + uint64_t(rkd) * B;
+#pragma unroll
+            for (int l = 0; l < B; ++l) out[j * B + l] = src[l];
+        }
+    }
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
+__device__ inline uint16_t f32_to_bf16_rne(float v)
+{
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return uint16_t((b >> 16) | 0x40u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return uint16_t(b >> 16);
+}
+
+}  // namespace muw

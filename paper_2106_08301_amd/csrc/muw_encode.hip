@@ -1,0 +1,629 @@
+// muw_encode.hip -- Unify() as a one-shot projection (paper Sec. 3.1, Sec. 3.3 Eq. 6, Sec. 4.3) and the
+// packing of its result into the device layout of muw_layout.hpp.
+//
+// Compile with -ffp-contract=off: the block scores decide the selection by their exact fp64 bit
+// patterns, so every multiply and add must be rounded separately and in the stated order.
+//
+// Steps (all on the caller's stream, no host round trips until the final flag read):
+//   scores   one thread per block: e_p = sum w^2, e_u = sum (|w| - q)^2 with q = (sum |w|)/B, fp64
+//   select   exact "k smallest by (key, block index)" by an 8-pass most-significant-byte radix
+//            select on the 64-bit patterns (non-negative doubles order like unsigned integers),
+//            then ties at the threshold value are taken in block-index order via a prefix count
+//   pack     per tile: count, prefix-sum the tile sizes into the directory, then one wavefront per
+//            tile writes masks, magnitudes, permuted sign bits and dense payload
+#include "muw_internal.hpp"
+
+namespace muw {
+
+namespace {
+
+constexpr int kChunk = 2048;  // blocks per workgroup in the tie-count / mark kernels (8 per thread)
+
+struct SelState {
+    uint64_t prefix;   // bits of the threshold key found so far
+    uint64_t k_rem;    // 0-based position of the threshold among the keys that match the prefix
+    uint32_t hist[256];
+    uint32_t nonfinite;
+    uint32_t pad;
+};
+
+struct TileCount {
+    uint32_t nU, nD;
+};
+
+__device__ inline double widen(float v) { return double(v); }
+__device__ inline double widen(bf16_t v) { return double(__uint_as_float(uint32_t(v.bits) << 16)); }
+
+// The B stored weights of block (n, kb), widened exactly to double.
+template <typename T, int B>
+__device__ inline void load_block(const T *W, int layout, int64_t n, int64_t kb, int64_t K, int Cin,
+                                  int KH, int KW, T *raw)
+{
+    if (layout == MUW_LAYOUT_NK) {
+        const T *p = W + n * K + kb * B;
+#pragma unroll
+        for (int l = 0; l < B; ++l) raw[l] = p[l];
+    } else {
+        int64_t k = kb * B;
+        int64_t tap = k / Cin, cin = k % Cin;
+        int64_t kh = tap / KW, kw = tap % KW;
+        const T *p = W + ((n * Cin + cin) * KH + kh) * KW + kw;
+        int64_t step = int64_t(KH) * KW;
+#pragma unroll
+        for (int l = 0; l < B; ++l) raw[l] = p[l * step];
+    }
+}
+
+// q = (sum |w_l|) / B, left to right, in double (Sec. 3.1).
+template <typename T, int B>
+__device__ inline double block_q(const T *raw)
+{
+    double s1 = 0.0;
+#pragma unroll
+    for (int l = 0; l < B; ++l) s1 = s1 + fabs(widen(raw[l]));
+    return s1 / double(B);
+}
+
+template <typename T, int B>
+__global__ __launch_bounds__(256) void k_scores(const T *W, int layout, int64_t N, int64_t K, int Cin,
+                                                int KH, int KW, uint64_t *key_p, uint64_t *key_u,
+                                                SelState *state)
+{
+    const int64_t KB = K / B;
+    const int64_t j = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= N * KB) return;
+    T raw[B];
+    load_block<T, B>(W, layout, j / KB, j % KB, K, Cin, KH, KW, raw);
+    bool bad = false;
+#pragma unroll
+    for (int l = 0; l < B; ++l) bad |= !isfinite(widen(raw[l]));
+    const double q = block_q<T, B>(raw);
+    double e_p = 0.0, e_u = 0.0;
+#pragma unroll
+    for (int l = 0; l < B; ++l) {
+        double w = widen(raw[l]);
+        double sq = w * w;
+        e_p = e_p + sq;
+    }
+#pragma unroll
+    for (int l = 0; l < B; ++l) {
+        double d = fabs(widen(raw[l])) - q;
+        double dd = d * d;
+        e_u = e_u + dd;
+    }
+    key_p[j] = uint64_t(__double_as_longlong(e_p));
+    key_u[j] = uint64_t(__double_as_longlong(e_u));
+    if (bad) atomicOr(&state->nonfinite, 1u);
+}
+
+__global__ void k_select_init(SelState *s, uint64_t k_rem)
+{
+    if (threadIdx.x == 0) {
+        s->prefix = 0;
+        s->k_rem = k_rem;
+    }
+    s->hist[threadIdx.x] = 0;
+}
+
+// Histogram of byte (key >> shift) over the keys whose higher bytes equal the prefix found so far.
+__global__ __launch_bounds__(256) void k_select_hist(const uint64_t *keys, int64_t NB, SelState *s,
+                                                     int shift)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint64_t prefix = s->prefix;
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t j = int64_t(blockIdx.x) * 256 + threadIdx.x; j < NB; j += stride) {
+        uint64_t key = keys[j];
+        bool match = (shift == 56) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
+        if (match) atomicAdd(&h[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(&s->hist[threadIdx.x], h[threadIdx.x]);
+}
+
+__global__ void k_select_pick(SelState *s, int shift)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = s->hist[threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t k = s->k_rem, cum = 0;
+        int b = 0;
+        for (; b < 255; ++b) {
+            if (cum + h[b] > k) break;
+            cum += h[b];
+        }
+        s->prefix |= uint64_t(b) << shift;
+        s->k_rem = k - cum;
+    }
+    s->hist[threadIdx.x] = 0;
+}
+
+// Number of keys equal to the threshold in each chunk of kChunk consecutive blocks.
+__global__ __launch_bounds__(256) void k_tie_count(const uint64_t *keys, int64_t NB, const SelState *s,
+                                                   uint32_t *chunk_counts)
+{
+    __shared__ uint32_t total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    const uint64_t T = s->prefix;
+    const int64_t base = int64_t(blockIdx.x) * kChunk + int64_t(threadIdx.x) * 8;
+    uint32_t c = 0;
+    for (int i = 0; i < 8; ++i)
+        if (base + i < NB && keys[base + i] == T) ++c;
+    if (c) atomicAdd(&total, c);
+    __syncthreads();
+    if (threadIdx.x == 0) chunk_counts[blockIdx.x] = total;
+}
+
+// In-place exclusive prefix sum of n values by one workgroup of 256 threads.
+__global__ __launch_bounds__(256) void k_exclusive_scan(uint32_t *v, int64_t n)
+{
+    __shared__ uint32_t part[256];
+    const int64_t per = (n + 255) / 256;
+    const int64_t lo = int64_t(threadIdx.x) * per, hi = (lo + per < n) ? lo + per : n;
+    uint32_t sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += v[i];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int i = 0; i < 256; ++i) {
+            uint32_t t = part[i];
+            part[i] = run;
+            run += t;
+        }
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (int64_t i = lo; i < hi; ++i) {
+        uint32_t t = v[i];
+        v[i] = run;
+        run += t;
+    }
+}
+
+// Tag every block whose key is below the threshold, and the first (k_rem + 1) blocks, in index
+// order, whose key equals it.  Selected blocks get `tag`; when `poison` is set their entry in
+// `other_keys` becomes all-ones so that the next selection can never pick them.
+__global__ __launch_bounds__(256) void k_mark(const uint64_t *keys, int64_t NB, const SelState *s,
+                                              const uint32_t *chunk_base, uint8_t *tags, uint8_t tag,
+                                              uint64_t *other_keys, int poison)
+{
+    __shared__ uint32_t scan[256];
+    const uint64_t T = s->prefix;
+    const uint64_t take = s->k_rem + 1;
+    const int64_t base = int64_t(blockIdx.x) * kChunk + int64_t(threadIdx.x) * 8;
+    uint32_t c = 0;
+    for (int i = 0; i < 8; ++i)
+        if (base + i < NB && keys[base + i] == T) ++c;
+    scan[threadIdx.x] = c;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        uint32_t add = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
+        __syncthreads();
+        scan[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint64_t rank = uint64_t(chunk_base[blockIdx.x]) + (scan[threadIdx.x] - c);
+    for (int i = 0; i < 8; ++i) {
+        const int64_t j = base + i;
+        if (j >= NB) break;
+        const uint64_t key = keys[j];
+        bool sel = key < T;
+        if (key == T) {
+            sel = rank < take;
+            ++rank;
+        }
+        if (sel) {
+            tags[j] = tag;
+            if (poison) other_keys[j] = ~uint64_t(0);
+        }
+    }
+}
+
+// One wavefront per tile: how many UNIFIED / DENSE blocks it holds.
+__global__ __launch_bounds__(256) void k_tile_count(const uint8_t *tags, Layout L, TileCount *counts)
+{
+    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= L.NT) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t strip = tile / L.KT, kt = tile % L.KT;
+    const int64_t kb0 = kt * (kTileK / L.B);
+    const int64_t kb1 = (kb0 + kTileK / L.B < L.KB) ? kb0 + kTileK / L.B : L.KB;
+    const int64_t width = kb1 - kb0;
+    uint32_t nU = 0, nD = 0;
+    for (int64_t i = lane; i < width * kStripRows; i += 64) {
+        const int64_t n = strip * kStripRows + i / width;
+        if (n >= L.N) break;
+        const uint8_t t = tags[n * L.KB + kb0 + i % width];
+        nU += (t == MUW_TAG_UNIFIED);
+        nD += (t == MUW_TAG_DENSE);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        nU += __shfl_down(nU, off);
+        nD += __shfl_down(nD, off);
+    }
+    if (lane == 0) {
+        counts[tile].nU = nU;
+        counts[tile].nD = nD;
+    }
+}
+
+// Directory = exclusive prefix sum of the tile stream sizes (one workgroup), plus the header.
+__global__ __launch_bounds__(256) void k_directory(const TileCount *counts, Layout L, uint8_t *blob,
+                                                   int64_t n_u, int64_t n_p)
+{
+    __shared__ uint64_t part[256];
+    DirEntry *dir = reinterpret_cast<DirEntry *>(blob + L.dir_off);
+    const int64_t per = (L.NT + 255) / 256;
+    const int64_t lo = int64_t(threadIdx.x) * per, hi = (lo + per < L.NT) ? lo + per : L.NT;
+    uint64_t sum = 0;
+    for (int64_t t = lo; t < hi; ++t)
+        sum += tile_bytes(L, panels_in_tile(L, t % L.KT), counts[t].nU, counts[t].nD);
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t run = 0;
+        for (int i = 0; i < 256; ++i) {
+            uint64_t t = part[i];
+            part[i] = run;
+            run += t;
+        }
+        dir[L.NT].off16 = uint32_t(run / 16);
+        dir[L.NT].nU = 0;
+        dir[L.NT].nD = 0;
+        uint64_t *h = reinterpret_cast<uint64_t *>(blob);
+        h[0] = uint64_t(kMagic) | (uint64_t(1) << 32);  // magic, layout version
+        h[1] = uint64_t(L.N);
+        h[2] = uint64_t(L.K);
+        h[3] = uint64_t(L.B) | (uint64_t(L.vb) << 32);
+        h[4] = uint64_t(n_u);
+        h[5] = uint64_t(n_p);
+        h[6] = L.streams_off;
+        h[7] = L.streams_off + run;  // total bytes
+    }
+    __syncthreads();
+    uint64_t run = part[threadIdx.x];
+    for (int64_t t = lo; t < hi; ++t) {
+        dir[t].off16 = uint32_t(run / 16);
+        dir[t].nU = uint16_t(counts[t].nU);
+        dir[t].nD = uint16_t(counts[t].nD);
+        run += tile_bytes(L, panels_in_tile(L, t % L.KT), counts[t].nU, counts[t].nD);
+    }
+}
+
+// fp64 -> bf16 bits, one rounding to nearest even, for finite q >= 0.
+__device__ inline uint16_t f64_to_bf16_rne(double q)
+{
+    const uint64_t b = uint64_t(__double_as_longlong(q));
+    const int e = int(b >> 52) & 0x7ff;
+    const uint64_t mant = b & ((uint64_t(1) << 52) - 1);
+    if (e == 0) return 0;            // zero or fp64 subnormal: far below half the smallest bf16
+    const int E = e - 1023 + 127;    // biased bf16 exponent
+    if (E >= 255) return 0x7f80;
+    if (E >= 1) {
+        uint32_t r = (uint32_t(E) << 7) | uint32_t(mant >> 45);
+        const uint64_t rem = mant & ((uint64_t(1) << 45) - 1), half = uint64_t(1) << 44;
+        if (rem > half || (rem == half && (r & 1u))) ++r;  // a carry runs into the exponent
+        return uint16_t(r);
+    }
+    // bf16 subnormal: multiples of 2^-133
+    const uint64_t full = (uint64_t(1) << 52) | mant;
+    const int sh = 942 - e;          // >= 46 here
+    if (sh > 54) return 0;
+    uint64_t r = full >> sh;
+    const uint64_t rem = full & ((uint64_t(1) << sh) - 1), half = uint64_t(1) << (sh - 1);
+    if (rem > half || (rem == half && (r & 1u))) ++r;
+    return uint16_t(r);
+}
+
+__device__ inline void store_mag(float *dst, double q) { *dst = float(q); }
+__device__ inline void store_mag(bf16_t *dst, double q) { dst->bits = f64_to_bf16_rne(q); }
+
+// One wavefront per tile writes the tile's stream.
+template <typename T, int B>
+__global__ __launch_bounds__(256) void k_pack(const T *W, int layout, int Cin, int KH, int KW,
+                                              const uint8_t *tags, Layout L, uint8_t *blob)
+{
+    constexpr int S = 16 / B;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= L.NT) return;
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t strip = tile / L.KT, kt = tile % L.KT;
+    const DirEntry de = reinterpret_cast<const DirEntry *>(blob + L.dir_off)[tile];
+    uint8_t *base = blob + L.streams_off + uint64_t(de.off16) * 16;
+    const int np = panels_in_tile(L, kt);
+    const TileStreams ts = tile_streams(B, int(sizeof(T)), np, de.nU, de.nD);
+    uint64_t *masks = reinterpret_cast<uint64_t *>(base);
+    T *dense = reinterpret_cast<T *>(base + ts.dense_off);
+    T *mags = reinterpret_cast<T *>(base + ts.mag_off);
+    const uint64_t sign_addr = reinterpret_cast<uint64_t>(base + ts.sign_off);
+    const int64_t n = strip * kStripRows + r;
+    uint32_t ru = 0, rd = 0;
+    for (int p = 0; p < np; ++p) {
+        for (int j = 0; j < S; ++j) {
+            const int64_t kb = (kt * kTilePanels + p) * (kPanelK / B) + S * g + j;
+            const bool valid = n < L.N && kb < L.KB;
+            const uint8_t tag = valid ? tags[n * L.KB + kb] : uint8_t(MUW_TAG_PRUNED);
+            const uint64_t mu = __ballot(tag == MUW_TAG_UNIFIED);
+            const uint64_t md = __ballot(tag == MUW_TAG_DENSE);
+            if (lane == 0) {
+                masks[p * 2 * S + j] = mu;
+                masks[p * 2 * S + S + j] = md;
+            }
+            const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
+            ru += __popcll(mu);
+            rd += __popcll(md);
+            if (tag == MUW_TAG_PRUNED) continue;
+            T raw[B];
+            load_block<T, B>(W, layout, n, kb, L.K, Cin, KH, KW, raw);
+            if (tag == MUW_TAG_DENSE) {
+#pragma unroll
+                for (int l = 0; l < B; ++l) dense[uint64_t(rkd) * B + l] = raw[l];
+            } else {
+                store_mag(&mags[rku], block_q<T, B>(raw));
+                uint32_t field = 0;
+#pragma unroll
+                for (int l = 0; l < B; ++l)
+                    if (widen(raw[l]) < 0.0) field |= 1u << sign_pos(B, l);
+                if (field) {
+                    const uint64_t bit = sign_addr * 8 + uint64_t(rku) * B;  // absolute bit address
+                    uint32_t *word = reinterpret_cast<uint32_t *>((bit >> 5) << 2);
+                    atomicOr(word, field << (bit & 31u));
+                }
+            }
+        }
+    }
+}
+
+// One wavefront per tile: the canonical (layout-independent) view.
+template <typename T, int B>
+__global__ __launch_bounds__(256) void k_export(const uint8_t *blob, Layout L, uint8_t *tags,
+                                                uint16_t *signs, T *mags_out)
+{
+    constexpr int S = 16 / B;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= L.NT) return;
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t strip = tile / L.KT, kt = tile % L.KT;
+    const DirEntry de = reinterpret_cast<const DirEntry *>(blob + L.dir_off)[tile];
+    const uint8_t *base = blob + L.streams_off + uint64_t(de.off16) * 16;
+    const int np = panels_in_tile(L, kt);
+    const TileStreams ts = tile_streams(B, int(sizeof(T)), np, de.nU, de.nD);
+    const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
+    const T *mags = reinterpret_cast<const T *>(base + ts.mag_off);
+    const int64_t n = strip * kStripRows + r;
+    uint32_t ru = 0;
+    for (int p = 0; p < np; ++p) {
+        for (int j = 0; j < S; ++j) {
+            const uint64_t mu = masks[p * 2 * S + j], md = masks[p * 2 * S + S + j];
+            const uint32_t rku = ru + mbcnt64(mu);
+            ru += __popcll(mu);
+            const int64_t kb = (kt * kTilePanels + p) * (kPanelK / B) + S * g + j;
+            if (n >= L.N || kb >= L.KB) continue;
+            const bool isU = (mu >> lane) & 1, isD = (md >> lane) & 1;
+            const int64_t idx = n * L.KB + kb;
+            if (tags) tags[idx] = isU ? MUW_TAG_UNIFIED : (isD ? MUW_TAG_DENSE : MUW_TAG_PRUNED);
+            uint32_t canon = 0;
+            T mag{};
+            if (isU) {
+                const uint32_t field = load_sign_field<B>(base + ts.sign_off, rku);
+#pragma unroll
+                for (int l = 0; l < B; ++l) canon |= ((field >> sign_pos(B, l)) & 1u) << l;
+                mag = mags[rku];
+            }
+            if (signs) signs[idx] = uint16_t(canon);
+            if (mags_out) mags_out[idx] = mag;
+        }
+    }
+}
+
+// One wavefront per tile: W^ in the GEMM view.
+template <typename T, int B>
+__global__ __launch_bounds__(256) void k_decode(const uint8_t *blob, Layout L, T *What)
+{
+    constexpr int S = 16 / B;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= L.NT) return;
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t strip = tile / L.KT, kt = tile % L.KT;
+    const DirEntry de = reinterpret_cast<const DirEntry *>(blob + L.dir_off)[tile];
+    const uint8_t *base = blob + L.streams_off + uint64_t(de.off16) * 16;
+    const int np = panels_in_tile(L, kt);
+    const TileStreams ts = tile_streams(B, int(sizeof(T)), np, de.nU, de.nD);
+    const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
+    const T *dense = reinterpret_cast<const T *>(base + ts.dense_off);
+    const T *mags = reinterpret_cast<const T *>(base + ts.mag_off);
+    const int64_t n = strip * kStripRows + r;
+    uint32_t ru = 0, rd = 0;
+    for (int p = 0; p < np; ++p) {
+        for (int j = 0; j < S; ++j) {
+            const uint64_t mu = masks[p * 2 * S + j], md = masks[p * 2 * S + S + j];
+            const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
+            ru += __popcll(mu);
+            rd += __popcll(md);
+            const int64_t kb = (kt * kTilePanels + p) * (kPanelK / B) + S * g + j;
+            if (n >= L.N || kb >= L.KB) continue;
+            const bool isU = (mu >> lane) & 1, isD = (md >> lane) & 1;
+            T *out = What + n * L.K + kb * B;
+            if (isD) {
+#pragma unroll
+                for (int l = 0; l < B; ++l) out[l] = dense[uint64_t(rkd) * B + l];
+            } else if (isU) {
+                const uint32_t field = load_sign_field<B>(base + ts.sign_off, rku);
+                const T mag = mags[rku];
+#pragma unroll
+                for (int l = 0; l < B; ++l) {
+                    T v = mag;
+                    if ((field >> sign_pos(B, l)) & 1u) {
+                        if constexpr (sizeof(T) == 2)
+                            v.bits ^= 0x8000u;
+                        else
+                            v = -v;
+                    }
+                    out[l] = v;
+                }
+            } else {
+#pragma unroll
+                for (int l = 0; l < B; ++l) out[l] = T{};
+            }
+        }
+    }
+}
+
+// Exact selection of the k smallest (key, index) among NB keys; selected blocks get `tag`.
+muw_status select_smallest(uint64_t *keys, int64_t NB, int64_t k, SelState *state, uint32_t *chunks,
+                           uint8_t *tags, uint8_t tag, uint64_t *other_keys, int poison,
+                           hipStream_t st)
+{
+    if (k <= 0) return MUW_OK;
+    const int64_t nchunks = (NB + kChunk - 1) / kChunk;
+    const int hist_grid = int(nchunks < 2048 ? nchunks : 2048);
+    k_select_init<<<1, 256, 0, st>>>(state, uint64_t(k - 1));
+    for (int shift = 56; shift >= 0; shift -= 8) {
+        k_select_hist<<<hist_grid, 256, 0, st>>>(keys, NB, state, shift);
+        k_select_pick<<<1, 256, 0, st>>>(state, shift);
+    }
+    k_tie_count<<<dim3(unsigned(nchunks)), 256, 0, st>>>(keys, NB, state, chunks);
+    k_exclusive_scan<<<1, 256, 0, st>>>(chunks, nchunks);
+    k_mark<<<dim3(unsigned(nchunks)), 256, 0, st>>>(keys, NB, state, chunks, tags, tag, other_keys,
+                                                     poison);
+    return hip_status(hipGetLastError());
+}
+
+template <typename T, int B>
+muw_status encode_typed(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
+                        int64_t n_p, uint8_t *blob, size_t blob_bytes, uint8_t *ws, hipStream_t st,
+                        bool *nonfinite)
+{
+    const EncodeWorkspace w = encode_workspace(L);
+    const int64_t NB = L.N * L.KB;
+    uint64_t *key_p = reinterpret_cast<uint64_t *>(ws + w.key_p_off);
+    uint64_t *key_u = reinterpret_cast<uint64_t *>(ws + w.key_u_off);
+    uint8_t *tags = ws + w.tags_off;
+    SelState *state = reinterpret_cast<SelState *>(ws + w.state_off);
+    uint32_t *chunks = reinterpret_cast<uint32_t *>(ws + w.chunk_off);
+    TileCount *tcnt = reinterpret_cast<TileCount *>(ws + w.tilecnt_off);
+
+    if (hipMemsetAsync(blob, 0, blob_bytes, st) != hipSuccess) return MUW_EHIP;
+    if (hipMemsetAsync(tags, MUW_TAG_DENSE, size_t(NB), st) != hipSuccess) return MUW_EHIP;
+    if (hipMemsetAsync(state, 0, sizeof(SelState), st) != hipSuccess) return MUW_EHIP;
+
+    const unsigned grid_blocks = unsigned((NB + 255) / 256);
+    k_scores<T, B><<<grid_blocks, 256, 0, st>>>(static_cast<const T *>(W), layout, L.N, L.K, d.Cin, d.KH,
+                                                d.KW, key_p, key_u, state);
+    muw_status rc = select_smallest(key_p, NB, n_p, state, chunks, tags, MUW_TAG_PRUNED, key_u, 1, st);
+    if (rc != MUW_OK) return rc;
+    rc = select_smallest(key_u, NB, n_u, state, chunks, tags, MUW_TAG_UNIFIED, nullptr, 0, st);
+    if (rc != MUW_OK) return rc;
+
+    const unsigned grid_tiles = unsigned((L.NT + 3) / 4);
+    k_tile_count<<<grid_tiles, 256, 0, st>>>(tags, L, tcnt);
+    k_directory<<<1, 256, 0, st>>>(tcnt, L, blob, n_u, n_p);
+    k_pack<T, B><<<grid_tiles, 256, 0, st>>>(static_cast<const T *>(W), layout, d.Cin, d.KH, d.KW, tags,
+                                             L, blob);
+    if (hipGetLastError() != hipSuccess) return MUW_EHIP;
+
+    uint32_t flag = 0;
+    if (hipMemcpyAsync(&flag, &state->nonfinite, sizeof(flag), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return MUW_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MUW_EHIP;
+    *nonfinite = flag != 0;
+    return MUW_OK;
+}
+
+template <typename T>
+muw_status encode_by_block(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
+                           int64_t n_p, uint8_t *blob, size_t blob_bytes, uint8_t *ws, hipStream_t st,
+                           bool *nonfinite)
+{
+    switch (d.B) {
+    case 4: return encode_typed<T, 4>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
+    case 8: return encode_typed<T, 8>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
+    case 16: return encode_typed<T, 16>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
+    default: return MUW_EUNSUPPORTED;
+    }
+}
+
+template <typename T, int B>
+void export_typed(const Layout &L, const void *blob, uint8_t *tags, uint16_t *signs, void *mags,
+                  hipStream_t st)
+{
+    k_export<T, B><<<unsigned((L.NT + 3) / 4), 256, 0, st>>>(static_cast<const uint8_t *>(blob), L, tags,
+                                                            signs, static_cast<T *>(mags));
+}
+
+template <typename T, int B>
+void decode_typed(const Layout &L, const void *blob, void *What, hipStream_t st)
+{
+    k_decode<T, B><<<unsigned((L.NT + 3) / 4), 256, 0, st>>>(static_cast<const uint8_t *>(blob), L,
+                                                            static_cast<T *>(What));
+}
+
+}  // namespace
+
+EncodeWorkspace encode_workspace(const Layout &L)
+{
+    EncodeWorkspace w;
+    const uint64_t NB = uint64_t(L.N) * uint64_t(L.KB);
+    const uint64_t nchunks = (NB + kChunk - 1) / kChunk;
+    uint64_t off = 0;
+    w.key_p_off = off;
+    off = align16(off + NB * 8);
+    w.key_u_off = off;
+    off = align16(off + NB * 8);
+    w.tags_off = off;
+    off = align16(off + NB);
+    w.state_off = off;
+    off = align16(off + sizeof(SelState));
+    w.chunk_off = off;
+    off = align16(off + nchunks * 4);
+    w.tilecnt_off = off;
+    off = align16(off + uint64_t(L.NT) * sizeof(TileCount));
+    w.total = off;
+    return w;
+}
+
+muw_status launch_encode(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
+                         int64_t n_p, void *blob, size_t blob_bytes, void *ws, hipStream_t st,
+                         bool *nonfinite)
+{
+    uint8_t *b = static_cast<uint8_t *>(blob), *w = static_cast<uint8_t *>(ws);
+    if (d.wdtype == MUW_BF16)
+        return encode_by_block<bf16_t>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite);
+    return encode_by_block<float>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite);
+}
+
+#define MUW_DISPATCH_TB(FN, ...)                                              \
+    do {                                                                      \
+        if (d.wdtype == MUW_BF16) {                                           \
+            if (d.B == 4) FN<bf16_t, 4>(__VA_ARGS__);                         \
+            else if (d.B == 8) FN<bf16_t, 8>(__VA_ARGS__);                    \
+            else if (d.B == 16) FN<bf16_t, 16>(__VA_ARGS__);                  \
+            else return MUW_EUNSUPPORTED;                                     \
+        } else {                                                              \
+            if (d.B == 4) FN<float, 4>(__VA_ARGS__);                          \
+            else if (d.B == 8) FN<float, 8>(__VA_ARGS__);                     \
+            else if (d.B == 16) FN<float, 16>(__VA_ARGS__);                   \
+            else return MUW_EUNSUPPORTED;                                     \
+        }                                                                     \
+    } while (0)
+
+muw_status launch_export(const muw_desc &d, const Layout &L, const void *blob, uint8_t *tags,
+                         uint16_t *signs, void *mags, hipStream_t st)
+{
+    MUW_DISPATCH_TB(export_typed, L, blob, tags, signs, mags, st);
+    return hip_status(hipGetLastError());
+}
+
+muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, void *What,
+                         hipStream_t st)
+{
+    MUW_DISPATCH_TB(decode_typed, L, blob, What, st);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace muw

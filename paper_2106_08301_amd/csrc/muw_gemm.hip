@@ -1,0 +1,251 @@
+// muw_gemm.hip -- Y = X * W^^T and the implicit-GEMM convolution straight from the encoded layer
+// (paper Sec. 3.2: pruned blocks are skipped, unified blocks are +-q, the layer is a blocked GEMM).
+//
+// Kernels in this file
+//   k_wave_gemm_*   one wavefront per (16 activation rows) x (16-row strip of W): the lane decodes its
+//                   16 weights of a panel directly into the MFMA B-operand registers and reads the
+//                   matching activations straight from global memory.  General (any M, N, K, ld,
+//                   alignment, linear or convolution gather); the reference kernel of the library.
+#include "muw_decode.hpp"
+#include "muw_internal.hpp"
+
+namespace muw {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// How the A operand (activations) is addressed: a dense row-major matrix, or an NCHW image gathered
+// as the im2col matrix with k = (kh*KW + kw)*Cin + cin (never materialised).
+struct ActView {
+    const void *X;
+    int64_t M, K, ldx;
+    int conv;  // 0: X[m][k] at X + m*ldx + k
+    int64_t Cin, H, W, OH, OW;
+    int32_t KW, stride, pad;
+    int vec_ok;  // linear: rows are 16-byte aligned, 8-element loads allowed
+};
+
+template <typename T>
+__device__ inline T act_at(const ActView &a, int64_t m, int64_t k)
+{
+    const T *X = static_cast<const T *>(a.X);
+    if (m >= a.M || k >= a.K) return T{};
+    if (!a.conv) return X[m * a.ldx + k];
+    const int64_t pix = a.OH * a.OW;
+    const int64_t b = m / pix, rem = m % pix, oh = rem / a.OW, ow = rem % a.OW;
+    const int64_t tap = k / a.Cin, cin = k % a.Cin, kh = tap / a.KW, kw = tap % a.KW;
+    const int64_t ih = oh * a.stride + kh - a.pad, iw = ow * a.stride + kw - a.pad;
+    if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) return T{};
+    return X[((b * a.Cin + cin) * a.H + ih) * a.W + iw];
+}
+
+// 8 consecutive k of activation row m as four bf16 pairs.
+__device__ inline uint4 act_load8_bf16(const ActView &a, int64_t m, int64_t k)
+{
+    if (!a.conv && a.vec_ok && m < a.M && k + 8 <= a.K)
+        return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.X) + m * a.ldx + k);
+    uint32_t v[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t lo = act_at<bf16_t>(a, m, k + 2 * d).bits, hi = act_at<bf16_t>(a, m, k + 2 * d + 1).bits;
+        v[d] = lo | (hi << 16);
+    }
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Where output element (m, n) lives: row-major Y[m][n], or NCHW Y[b][n][oh][ow].
+struct OutView {
+    void *Y;
+    int64_t M, N, ldy;
+    int conv;
+    int64_t pix;  // OH*OW
+    int ydtype;
+};
+
+__device__ inline void store_out(const OutView &o, int64_t m, int64_t n, float v)
+{
+    if (m >= o.M || n >= o.N) return;
+    int64_t idx;
+    if (!o.conv) {
+        idx = m * o.ldy + n;
+    } else {
+        const int64_t b = m / o.pix, p = m % o.pix;
+        idx = (b * o.N + n) * o.pix + p;
+    }
+    if (o.ydtype == MUW_F32)
+        static_cast<float *>(o.Y)[idx] = v;
+    else
+        static_cast<uint16_t *>(o.Y)[idx] = f32_to_bf16_rne(v);
+}
+
+struct GroupPtrs {
+    const void *const *blobs;
+    const void *const *Xs;
+    void *const *Ys;
+};
+
+template <int B>
+__global__ __launch_bounds__(256) void k_wave_gemm_bf16(const uint8_t *blob, Layout L, ActView av,
+                                                        OutView ov, GroupPtrs gp)
+{
+    if (gp.blobs) {
+        blob = static_cast<const uint8_t *>(gp.blobs[blockIdx.z]);
+        av.X = gp.Xs[blockIdx.z];
+        ov.Y = gp.Ys[blockIdx.z];
+    }
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t mt = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (mt * 16 >= av.M) return;
+    const int64_t strip = blockIdx.y;
+    const DirEntry *dir = reinterpret_cast<const DirEntry *>(blob + L.dir_off);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t kt = 0; kt < L.KT; ++kt) {
+        const DirEntry de = dir[strip * L.KT + kt];
+        const uint8_t *tile = blob + L.streams_off + uint64_t(de.off16) * 16;
+        const int np = panels_in_tile(L, kt);
+        const TileStreams ts = tile_streams(B, 2, np, de.nU, de.nD);
+        uint32_t ru = 0, rd = 0;
+        for (int p = 0; p < np; ++p) {
+            uint32_t w[8];
+            decode_panel_bf16<B>(tile, ts, p, ru, rd, lane, w);
+            const int64_t k0 = (kt * kTilePanels + p) * kPanelK + 16 * g;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint4 a = act_load8_bf16(av, mt * 16 + r, k0 + 8 * h);
+                const uint4 b = make_uint4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                              __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) store_out(ov, mt * 16 + 4 * g + v, strip * 16 + r, acc[v]);
+}
+
+template <int B>
+__global__ __launch_bounds__(256) void k_wave_gemm_f32(const uint8_t *blob, Layout L, ActView av,
+                                                       OutView ov, GroupPtrs gp)
+{
+    if (gp.blobs) {
+        blob = static_cast<const uint8_t *>(gp.blobs[blockIdx.z]);
+        av.X = gp.Xs[blockIdx.z];
+        ov.Y = gp.Ys[blockIdx.z];
+    }
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t mt = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (mt * 16 >= av.M) return;
+    const int64_t strip = blockIdx.y;
+    const DirEntry *dir = reinterpret_cast<const DirEntry *>(blob + L.dir_off);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t kt = 0; kt < L.KT; ++kt) {
+        const DirEntry de = dir[strip * L.KT + kt];
+        const uint8_t *tile = blob + L.streams_off + uint64_t(de.off16) * 16;
+        const int np = panels_in_tile(L, kt);
+        const TileStreams ts = tile_streams(B, 4, np, de.nU, de.nD);
+        uint32_t ru = 0, rd = 0;
+        for (int p = 0; p < np; ++p) {
+            float w[16];
+            decode_panel_f32<B>(tile, ts, p, ru, rd, lane, w);
+            const int64_t k0 = (kt * kTilePanels + p) * kPanelK + 16 * g;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                // the 4 contraction slots of this MFMA are the lane groups g: slot g = k0 + e
+                const float a = act_at<float>(av, mt * 16 + r, k0 + e);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, w[e], acc, 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) store_out(ov, mt * 16 + 4 * g + v, strip * 16 + r, acc[v]);
+}
+
+template <int B>
+muw_status run_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t *blob, const ActView &av,
+                         const OutView &ov, const GroupPtrs &gp, int G, hipStream_t st)
+{
+    const int64_t mtiles = (av.M + 15) / 16;
+    dim3 grid(unsigned((mtiles + 3) / 4), unsigned(L.NS), unsigned(G));
+    if (d.wdtype == MUW_BF16)
+        k_wave_gemm_bf16<B><<<grid, 256, 0, st>>>(blob, L, av, ov, gp);
+    else
+        k_wave_gemm_f32<B><<<grid, 256, 0, st>>>(blob, L, av, ov, gp);
+    return hip_status(hipGetLastError());
+}
+
+muw_status dispatch_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t *blob, const ActView &av,
+                              const OutView &ov, const GroupPtrs &gp, int G, hipStream_t st)
+{
+    if (L.NS > 65535) return MUW_EUNSUPPORTED;
+    switch (d.B) {
+    case 4: return run_wave_gemm<4>(d, L, blob, av, ov, gp, G, st);
+    case 8: return run_wave_gemm<8>(d, L, blob, av, ov, gp, G, st);
+    case 16: return run_wave_gemm<16>(d, L, blob, av, ov, gp, G, st);
+    default: return MUW_EUNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+size_t gemm_workspace_bytes(const muw_desc &, const Layout &, int64_t) { return 0; }
+
+muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *, size_t,
+                       hipStream_t st)
+{
+    if (a.M == 0) return MUW_OK;
+    ActView av{};
+    av.X = a.X;
+    av.M = a.M;
+    av.K = L.K;
+    av.ldx = a.ldx;
+    av.conv = 0;
+    av.vec_ok = (a.ldx % 8 == 0) && (a.blobs || (reinterpret_cast<uintptr_t>(a.X) % 16 == 0));
+    OutView ov{};
+    ov.Y = a.Y;
+    ov.M = a.M;
+    ov.N = L.N;
+    ov.ldy = a.ldy;
+    ov.conv = 0;
+    ov.ydtype = a.ydtype;
+    GroupPtrs gp{a.blobs, a.Xs, a.Ys};
+    return dispatch_wave_gemm(d, L, static_cast<const uint8_t *>(a.blob), av, ov, gp, a.blobs ? a.G : 1,
+                              st);
+}
+
+size_t conv2d_workspace_bytes(const muw_desc &, const Layout &, int64_t, int64_t, int64_t, int32_t,
+                              int32_t)
+{
+    return 0;
+}
+
+muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, void *, size_t,
+                         hipStream_t st)
+{
+    const int64_t M = a.Nb * a.OH * a.OW;
+    if (M == 0) return MUW_OK;
+    ActView av{};
+    av.X = a.X;
+    av.M = M;
+    av.K = L.K;
+    av.conv = 1;
+    av.Cin = d.Cin;
+    av.H = a.H;
+    av.W = a.W;
+    av.OH = a.OH;
+    av.OW = a.OW;
+    av.KW = d.KW;
+    av.stride = a.stride;
+    av.pad = a.pad;
+    OutView ov{};
+    ov.Y = a.Y;
+    ov.M = M;
+    ov.N = L.N;
+    ov.conv = 1;
+    ov.pix = a.OH * a.OW;
+    ov.ydtype = a.ydtype;
+    GroupPtrs gp{nullptr, nullptr, nullptr};
+    return dispatch_wave_gemm(d, L, static_cast<const uint8_t *>(a.blob), av, ov, gp, 1, st);
+}
+
+}  // namespace muw

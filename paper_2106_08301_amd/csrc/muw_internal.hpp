@@ -1,0 +1,62 @@
+// muw_internal.hpp -- launch entry points shared by the translation units of libmuw (not public).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/muw.h"
+#include "muw_layout.hpp"
+
+namespace muw {
+
+inline int value_bytes(int dtype) { return dtype == MUW_BF16 ? 2 : 4; }
+
+// Element types as they sit in memory: fp32, or the 16 bits of a bfloat16.
+struct bf16_t {
+    uint16_t bits;
+};
+
+// Workspace carve-up of muw_encode.
+struct EncodeWorkspace {
+    uint64_t key_p_off, key_u_off, tags_off, state_off, chunk_off, tilecnt_off, total;
+};
+EncodeWorkspace encode_workspace(const Layout &L);
+
+muw_status launch_encode(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
+                         int64_t n_p, void *blob, size_t blob_bytes, void *ws, hipStream_t st,
+                         bool *nonfinite);
+muw_status launch_export(const muw_desc &d, const Layout &L, const void *blob, uint8_t *tags,
+                         uint16_t *signs, void *mags, hipStream_t st);
+muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, void *What,
+                         hipStream_t st);
+
+struct GemmArgs {
+    const void *blob;        // single problem
+    const void *X;
+    void *Y;
+    const void *const *blobs;  // grouped problems (device arrays), or null
+    const void *const *Xs;
+    void *const *Ys;
+    int32_t G;
+    int64_t M, ldx, ldy;
+    int ydtype;
+};
+muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *ws, size_t ws_bytes,
+                       hipStream_t st);
+size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M);
+
+struct ConvArgs {
+    const void *blob;
+    const void *X;
+    void *Y;
+    int64_t Nb, H, W, OH, OW;
+    int32_t stride, pad;
+    int ydtype;
+};
+muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, void *ws, size_t ws_bytes,
+                         hipStream_t st);
+size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, int64_t H, int64_t W,
+                              int32_t stride, int32_t pad);
+
+inline muw_status hip_status(hipError_t e) { return e == hipSuccess ? MUW_OK : MUW_EHIP; }
+
+}  // namespace muw

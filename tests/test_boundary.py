@@ -1,0 +1,85 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on
+the host before touching the GPU (runs without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def muw():
+    from paper_2106_08301_amd import build
+    build.build()
+    from paper_2106_08301_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(muw):
+    header = open(os.path.join(ROOT, "include", "muw.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(muw_[a-z0-9_]+)\s*\(", header)))
+    assert declared == sorted(muw.EXPORTED)
+    for name in declared:
+        assert hasattr(muw.lib, name), name
+
+
+def test_version_and_status_strings(muw):
+    assert muw.muw_version() >= 1
+    assert muw.status_str(muw.MUW_OK) == "ok"
+    assert len({muw.status_str(s) for s in range(7)}) == 7
+
+
+def test_counts_match_hand_values(muw):
+    assert muw.muw_counts(9216, 0.6, 0.3) == (5530, 2765)
+    assert muw.muw_counts(1048576, 0.7, 0.25) == (734003, 262144)
+    assert muw.muw_counts(5636096, 0.4, 0.5) == (2254438, 2818048)
+    assert muw.muw_counts(10, 1.0, 1.0) == (0, 10)
+    with pytest.raises(muw.MuwError):
+        muw.muw_counts(10, -0.1, 0.0)
+
+
+def test_sizes_and_compressed_bytes(muw):
+    d = muw.make_desc(4096, 4096, 16, muw.MUW_BF16)
+    blob, ws = muw.muw_encode_sizes(d, 0.7, 0.25)
+    d.n_unified, d.n_pruned = muw.muw_counts(4096 * 256, 0.7, 0.25)
+    algo = muw.lib.muw_compressed_bytes(C.byref(d))
+    # 2 bits per block + (16 + 16) bits per unified block + 16*16 bits per dense block
+    assert algo == (2 * 1048576 + 734003 * 32 + 52429 * 256) // 8
+    assert algo <= blob <= algo * 1.02             # directory, masks of ragged panels, padding
+    assert ws > 0
+
+
+def test_bad_arguments_are_rejected_on_the_host(muw):
+    sz = C.c_size_t()
+    fake = C.c_void_p(0x1000)                      # never dereferenced: checks fail first
+    bad_shape = muw.make_desc(64, 100, 8, muw.MUW_BF16)          # K % B != 0
+    assert muw.lib.muw_encode_sizes(C.byref(bad_shape), 0.5, 0.2, C.byref(sz), C.byref(sz)) == muw.MUW_ESHAPE
+    bad_block = muw.make_desc(64, 96, 3, muw.MUW_BF16)           # unsupported block length
+    assert muw.lib.muw_encode_sizes(C.byref(bad_block), 0.5, 0.2, C.byref(sz), C.byref(sz)) == muw.MUW_EUNSUPPORTED
+    conv = muw.make_desc(64, 64 * 9, 8, muw.MUW_BF16, 3, 3, 60)  # KH*KW*Cin != K
+    assert muw.lib.muw_encode_sizes(C.byref(conv), 0.5, 0.2, C.byref(sz), C.byref(sz)) == muw.MUW_ESHAPE
+    ok = muw.make_desc(64, 128, 8, muw.MUW_BF16)
+    assert muw.lib.muw_encode_sizes(C.byref(ok), 1.5, 0.2, C.byref(sz), C.byref(sz)) == muw.MUW_EINVAL
+    assert muw.lib.muw_encode(C.byref(ok), None, 0, 0.5, 0.2, fake, 1 << 20, fake, 1 << 20, None) == muw.MUW_EINVAL
+    assert muw.lib.muw_encode(C.byref(ok), fake, 0, 0.5, 0.2, fake, 16, fake, 1 << 20, None) == muw.MUW_ENOSPC
+    assert muw.lib.muw_encode(C.byref(ok), C.c_void_p(0x1004), 0, 0.5, 0.2, fake, 1 << 20, fake, 1 << 20,
+                              None) == muw.MUW_EINVAL            # misaligned weights
+    # gemm: leading dimensions, dtype mix, null pointers
+    g = muw.lib.muw_gemm
+    assert g(C.byref(ok), fake, fake, muw.MUW_BF16, 4, 100, fake, muw.MUW_F32, 64, None, 0, None) == muw.MUW_ESHAPE
+    assert g(C.byref(ok), fake, fake, muw.MUW_BF16, 4, 128, fake, muw.MUW_F32, 60, None, 0, None) == muw.MUW_ESHAPE
+    assert g(C.byref(ok), fake, fake, muw.MUW_F32, 4, 128, fake, muw.MUW_F32, 64, None, 0, None) == muw.MUW_EUNSUPPORTED
+    assert g(C.byref(ok), None, fake, muw.MUW_BF16, 4, 128, fake, muw.MUW_F32, 64, None, 0, None) == muw.MUW_EINVAL
+    assert g(C.byref(ok), fake, fake, muw.MUW_BF16, -1, 128, fake, muw.MUW_F32, 64, None, 0, None) == muw.MUW_EINVAL
+    assert g(C.byref(ok), None, None, muw.MUW_BF16, 0, 128, None, muw.MUW_F32, 64, None, 0, None) == muw.MUW_OK
+    gg = muw.lib.muw_gemm_grouped
+    assert gg(C.byref(ok), 4, fake, fake, muw.MUW_BF16, 17, fake, muw.MUW_F32, None) == muw.MUW_EUNSUPPORTED
+    assert gg(C.byref(ok), 4, None, fake, muw.MUW_BF16, 8, fake, muw.MUW_F32, None) == muw.MUW_EINVAL
+    cv = muw.make_desc(64, 64 * 9, 8, muw.MUW_BF16, 3, 3, 64)
+    c2 = muw.lib.muw_conv2d
+    assert c2(C.byref(cv), fake, fake, muw.MUW_BF16, 2, 8, 8, 0, 1, fake, muw.MUW_F32, None, 0, None) == muw.MUW_EINVAL
+    assert c2(C.byref(cv), fake, fake, muw.MUW_BF16, 2, 1, 1, 1, 0, fake, muw.MUW_F32, None, 0, None) == muw.MUW_ESHAPE
+    assert c2(C.byref(cv), fake, None, muw.MUW_BF16, 2, 8, 8, 1, 1, fake, muw.MUW_F32, None, 0, None) == muw.MUW_EINVAL
