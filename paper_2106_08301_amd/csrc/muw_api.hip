@@ -104,12 +104,14 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
     int64_t n_u, n_p;
     muw_counts(L.N * L.KB, r_unify, r_prune, &n_u, &n_p);
     bool nonfinite = false;
+    int32_t max_tile = 0;
     rc = launch_encode(*desc, L, W_dev, int(layout), n_u, n_p, blob_dev, need_blob, ws_dev,
-                       static_cast<hipStream_t>(hip_stream), &nonfinite);
+                       static_cast<hipStream_t>(hip_stream), &nonfinite, &max_tile);
     if (rc != MUW_OK) return rc;
     if (nonfinite) return MUW_ENONFINITE;
     desc->n_unified = n_u;
     desc->n_pruned = n_p;
+    desc->max_tile_bytes = max_tile;
     return MUW_OK;
 }
 

@@ -24,7 +24,7 @@ struct SelState {
     uint64_t k_rem;    // 0-based position of the threshold among the keys that match the prefix
     uint32_t hist[256];
     uint32_t nonfinite;
-    uint32_t pad;
+    uint32_t max_tile_bytes;
 };
 
 struct TileCount {
@@ -254,18 +254,27 @@ __global__ __launch_bounds__(256) void k_tile_count(const uint8_t *tags, Layout 
 
 // Directory = exclusive prefix sum of the tile stream sizes (one workgroup), plus the header.
 __global__ __launch_bounds__(256) void k_directory(const TileCount *counts, Layout L, uint8_t *blob,
-                                                   int64_t n_u, int64_t n_p)
+                                                   int64_t n_u, int64_t n_p, SelState *state)
 {
     __shared__ uint64_t part[256];
+    __shared__ uint32_t biggest;
+    if (threadIdx.x == 0) biggest = 0;
+    __syncthreads();
     DirEntry *dir = reinterpret_cast<DirEntry *>(blob + L.dir_off);
     const int64_t per = (L.NT + 255) / 256;
     const int64_t lo = int64_t(threadIdx.x) * per, hi = (lo + per < L.NT) ? lo + per : L.NT;
     uint64_t sum = 0;
-    for (int64_t t = lo; t < hi; ++t)
-        sum += tile_bytes(L, panels_in_tile(L, t % L.KT), counts[t].nU, counts[t].nD);
+    uint32_t mx = 0;
+    for (int64_t t = lo; t < hi; ++t) {
+        const uint32_t b = tile_bytes(L, panels_in_tile(L, t % L.KT), counts[t].nU, counts[t].nD);
+        sum += b;
+        mx = b > mx ? b : mx;
+    }
     part[threadIdx.x] = sum;
+    atomicMax(&biggest, mx);
     __syncthreads();
     if (threadIdx.x == 0) {
+        state->max_tile_bytes = biggest;
         uint64_t run = 0;
         for (int i = 0; i < 256; ++i) {
             uint64_t t = part[i];
@@ -497,7 +506,7 @@ muw_status select_smallest(uint64_t *keys, int64_t NB, int64_t k, SelState *stat
 template <typename T, int B>
 muw_status encode_typed(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
                         int64_t n_p, uint8_t *blob, size_t blob_bytes, uint8_t *ws, hipStream_t st,
-                        bool *nonfinite)
+                        bool *nonfinite, int32_t *max_tile_bytes)
 {
     const EncodeWorkspace w = encode_workspace(L);
     const int64_t NB = L.N * L.KB;
@@ -522,28 +531,29 @@ muw_status encode_typed(const muw_desc &d, const Layout &L, const void *W, int l
 
     const unsigned grid_tiles = unsigned((L.NT + 3) / 4);
     k_tile_count<<<grid_tiles, 256, 0, st>>>(tags, L, tcnt);
-    k_directory<<<1, 256, 0, st>>>(tcnt, L, blob, n_u, n_p);
+    k_directory<<<1, 256, 0, st>>>(tcnt, L, blob, n_u, n_p, state);
     k_pack<T, B><<<grid_tiles, 256, 0, st>>>(static_cast<const T *>(W), layout, d.Cin, d.KH, d.KW, tags,
                                              L, blob);
     if (hipGetLastError() != hipSuccess) return MUW_EHIP;
 
-    uint32_t flag = 0;
-    if (hipMemcpyAsync(&flag, &state->nonfinite, sizeof(flag), hipMemcpyDeviceToHost, st) != hipSuccess)
+    uint32_t result[2] = {0, 0};  // nonfinite, max_tile_bytes (adjacent in SelState)
+    if (hipMemcpyAsync(result, &state->nonfinite, sizeof(result), hipMemcpyDeviceToHost, st) != hipSuccess)
         return MUW_EHIP;
     if (hipStreamSynchronize(st) != hipSuccess) return MUW_EHIP;
-    *nonfinite = flag != 0;
+    *nonfinite = result[0] != 0;
+    *max_tile_bytes = int32_t(result[1]);
     return MUW_OK;
 }
 
 template <typename T>
 muw_status encode_by_block(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
                            int64_t n_p, uint8_t *blob, size_t blob_bytes, uint8_t *ws, hipStream_t st,
-                           bool *nonfinite)
+                           bool *nonfinite, int32_t *max_tile_bytes)
 {
     switch (d.B) {
-    case 4: return encode_typed<T, 4>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
-    case 8: return encode_typed<T, 8>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
-    case 16: return encode_typed<T, 16>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite);
+    case 4: return encode_typed<T, 4>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite, max_tile_bytes);
+    case 8: return encode_typed<T, 8>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite, max_tile_bytes);
+    case 16: return encode_typed<T, 16>(d, L, W, layout, n_u, n_p, blob, blob_bytes, ws, st, nonfinite, max_tile_bytes);
     default: return MUW_EUNSUPPORTED;
     }
 }
@@ -589,12 +599,12 @@ EncodeWorkspace encode_workspace(const Layout &L)
 
 muw_status launch_encode(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
                          int64_t n_p, void *blob, size_t blob_bytes, void *ws, hipStream_t st,
-                         bool *nonfinite)
+                         bool *nonfinite, int32_t *max_tile_bytes)
 {
     uint8_t *b = static_cast<uint8_t *>(blob), *w = static_cast<uint8_t *>(ws);
     if (d.wdtype == MUW_BF16)
-        return encode_by_block<bf16_t>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite);
-    return encode_by_block<float>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite);
+        return encode_by_block<bf16_t>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite, max_tile_bytes);
+    return encode_by_block<float>(d, L, W, layout, n_u, n_p, b, blob_bytes, w, st, nonfinite, max_tile_bytes);
 }
 
 #define MUW_DISPATCH_TB(FN, ...)                                              \

@@ -188,12 +188,20 @@ muw_status dispatch_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t 
 
 }  // namespace
 
-size_t gemm_workspace_bytes(const muw_desc &, const Layout &, int64_t) { return 0; }
+size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M)
+{
+    if (d.wdtype == MUW_BF16 && M >= 1 && M <= 16) return stream_gemm_workspace_bytes(L, M, 1);
+    return 0;
+}
 
-muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *, size_t,
+muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *ws, size_t ws_bytes,
                        hipStream_t st)
 {
     if (a.M == 0) return MUW_OK;
+    if (stream_gemm_applicable(d, L, a)) {
+        const size_t need = stream_gemm_workspace_bytes(L, a.M, a.blobs ? a.G : 1);
+        if (need == 0 || (ws && ws_bytes >= need && !a.blobs)) return launch_stream_gemm(d, L, a, ws, st);
+    }
     ActView av{};
     av.X = a.X;
     av.M = a.M;

@@ -23,7 +23,7 @@ EncodeWorkspace encode_workspace(const Layout &L);
 
 muw_status launch_encode(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
                          int64_t n_p, void *blob, size_t blob_bytes, void *ws, hipStream_t st,
-                         bool *nonfinite);
+                         bool *nonfinite, int32_t *max_tile_bytes);
 muw_status launch_export(const muw_desc &d, const Layout &L, const void *blob, uint8_t *tags,
                          uint16_t *signs, void *mags, hipStream_t st);
 muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, void *What,
@@ -43,6 +43,11 @@ struct GemmArgs {
 muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *ws, size_t ws_bytes,
                        hipStream_t st);
 size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M);
+
+// muw_stream.hip: the M <= 16 bandwidth-bound kernel
+bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a);
+size_t stream_gemm_workspace_bytes(const Layout &L, int64_t M, int G);
+muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *ws, hipStream_t st);
 
 struct ConvArgs {
     const void *blob;
