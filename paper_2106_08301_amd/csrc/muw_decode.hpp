@@ -17,7 +17,6 @@ __device__ inline void decode_panel_bf16(const uint8_t *tile, const TileStreams 
 {
     constexpr int S = 16 / B;
     const uint64_t *masks = reinterpret_cast<const uint64_t *>(tile) + panel * 2 * S;
-    const uint16_t *mags = reinterpret_cast<const uint16_t *>(tile + ts.mag_off);
 #pragma unroll
     for (int j = 0; j < S; ++j) {
         const uint64_t mu = masks[j], md = masks[S + j];
@@ -25,10 +24,7 @@ __device__ inline void decode_panel_bf16(const uint8_t *tile, const TileStreams 
         ru += __popcll(mu);
         rd += __popcll(md);
         uint32_t q = 0, s = 0;
-        if ((mu >> lane) & 1) {
-            q = mags[rku];
-            s = load_sign_field<B>(tile + ts.sign_off, rku);
-        }
+        if ((mu >> lane) & 1) load_unified<B, 2>(tile, ts, rku, q, s);
         decode_block_bf16<B>(q, s, out + j * (B / 2));
         if ((md >> lane) & 1) {
             const uint32_t *src = reinterpret_cast<const uint32_t *>(tile + ts.dense_off) + rkd * (B / 2);
@@ -45,7 +41,6 @@ __device__ inline void decode_panel_f32(const uint8_t *tile, const TileStreams &
 {
     constexpr int S = 16 / B;
     const uint64_t *masks = reinterpret_cast<const uint64_t *>(tile) + panel * 2 * S;
-    const uint32_t *mags = reinterpret_cast<const uint32_t *>(tile + ts.mag_off);
 #pragma unroll
     for (int j = 0; j < S; ++j) {
         const uint64_t mu = masks[j], md = masks[S + j];
@@ -53,10 +48,7 @@ __device__ inline void decode_panel_f32(const uint8_t *tile, const TileStreams &
         ru += __popcll(mu);
         rd += __popcll(md);
         uint32_t q = 0, s = 0;
-        if ((mu >> lane) & 1) {
-            q = mags[rku];
-            s = load_sign_field<B>(tile + ts.sign_off, rku);
-        }
+        if ((mu >> lane) & 1) load_unified<B, 4>(tile, ts, rku, q, s);
 #pragma unroll
         for (int l = 0; l < B; ++l)
             out[j * B + l] = __uint_as_float(q ^ (((s >> sign_pos(B, l)) & 1u) << 31));

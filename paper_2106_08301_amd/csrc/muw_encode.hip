@@ -329,6 +329,15 @@ __device__ inline uint16_t f64_to_bf16_rne(double q)
     return uint16_t(r);
 }
 
+template <typename T>
+__device__ inline T bits_to_value(uint32_t bits)
+{
+    if constexpr (sizeof(T) == 2)
+        return T{uint16_t(bits)};
+    else
+        return __uint_as_float(bits);
+}
+
 __device__ inline void store_mag(float *dst, double q) { *dst = float(q); }
 __device__ inline void store_mag(bf16_t *dst, double q) { dst->bits = f64_to_bf16_rne(q); }
 
@@ -373,11 +382,19 @@ __global__ __launch_bounds__(256) void k_pack(const T *W, int layout, int Cin, i
 #pragma unroll
                 for (int l = 0; l < B; ++l) dense[uint64_t(rkd) * B + l] = raw[l];
             } else {
-                store_mag(&mags[rku], block_q<T, B>(raw));
                 uint32_t field = 0;
 #pragma unroll
                 for (int l = 0; l < B; ++l)
                     if (widen(raw[l]) < 0.0) field |= 1u << sign_pos(B, l);
+                if constexpr (interleaved_records(B, int(sizeof(T)))) {
+                    T mag;
+                    store_mag(&mag, block_q<T, B>(raw));
+                    uint32_t qbits = 0;
+                    if constexpr (sizeof(T) == 2) qbits = mag.bits;
+                    reinterpret_cast<uint32_t *>(mags)[rku] = qbits | (field << 16);
+                    continue;
+                }
+                store_mag(&mags[rku], block_q<T, B>(raw));
                 if (field) {
                     const uint64_t bit = sign_addr * 8 + uint64_t(rku) * B;  // absolute bit address
                     uint32_t *word = reinterpret_cast<uint32_t *>((bit >> 5) << 2);
@@ -403,7 +420,6 @@ __global__ __launch_bounds__(256) void k_export(const uint8_t *blob, Layout L, u
     const int np = panels_in_tile(L, kt);
     const TileStreams ts = tile_streams(B, int(sizeof(T)), np, de.nU, de.nD);
     const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
-    const T *mags = reinterpret_cast<const T *>(base + ts.mag_off);
     const int64_t n = strip * kStripRows + r;
     uint32_t ru = 0;
     for (int p = 0; p < np; ++p) {
@@ -419,10 +435,11 @@ __global__ __launch_bounds__(256) void k_export(const uint8_t *blob, Layout L, u
             uint32_t canon = 0;
             T mag{};
             if (isU) {
-                const uint32_t field = load_sign_field<B>(base + ts.sign_off, rku);
+                uint32_t qbits, field;
+                load_unified<B, int(sizeof(T))>(base, ts, rku, qbits, field);
 #pragma unroll
                 for (int l = 0; l < B; ++l) canon |= ((field >> sign_pos(B, l)) & 1u) << l;
-                mag = mags[rku];
+                mag = bits_to_value<T>(qbits);
             }
             if (signs) signs[idx] = uint16_t(canon);
             if (mags_out) mags_out[idx] = mag;
@@ -445,7 +462,6 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t *blob, Layout L, T
     const TileStreams ts = tile_streams(B, int(sizeof(T)), np, de.nU, de.nD);
     const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
     const T *dense = reinterpret_cast<const T *>(base + ts.dense_off);
-    const T *mags = reinterpret_cast<const T *>(base + ts.mag_off);
     const int64_t n = strip * kStripRows + r;
     uint32_t ru = 0, rd = 0;
     for (int p = 0; p < np; ++p) {
@@ -462,8 +478,9 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t *blob, Layout L, T
 #pragma unroll
                 for (int l = 0; l < B; ++l) out[l] = dense[uint64_t(rkd) * B + l];
             } else if (isU) {
-                const uint32_t field = load_sign_field<B>(base + ts.sign_off, rku);
-                const T mag = mags[rku];
+                uint32_t qbits, field;
+                load_unified<B, int(sizeof(T))>(base, ts, rku, qbits, field);
+                const T mag = bits_to_value<T>(qbits);
 #pragma unroll
                 for (int l = 0; l < B; ++l) {
                     T v = mag;

@@ -12,10 +12,14 @@
 // A tile's byte stream (16-byte aligned, padded to 16 bytes):
 //   masks   per panel: U[0..S-1] then D[0..S-1], 64-bit each; bit l of U[j] / D[j] says that lane l's
 //           block j is UNIFIED / DENSE.  Neither bit: PRUNED (or outside the matrix).  2 bits per block.
+//           The mask area always spans 8 panels (a ragged last tile has zero masks for the panels it
+//           lacks), so payload offsets do not depend on the tile's position.
 //   dense   the B values of each DENSE block, in (panel, sub-step, lane) order
 //   mags    one stored magnitude per UNIFIED block, same order
 //   signs   B bits per UNIFIED block, same order, bit-packed; inside a block the bits are permuted
 //           (sign_pos) so that the bf16 decode is one shift and one bit-select per output dword
+//           (B = 16 with bf16 storage: mags and signs are interleaved instead, one 32-bit record
+//           {magnitude, sign field} per UNIFIED block, so a block costs a single 4-byte read)
 // Because payload order is (panel, sub-step, lane), the payload index of a lane's block is the
 // running count of earlier blocks plus the popcount of the mask below the lane (v_mbcnt): PRUNED
 // blocks cost 2 mask bits and nothing else (Sec. 3.1: storage of pruned blocks is skipped).
@@ -80,7 +84,8 @@ __host__ __device__ inline int panels_in_tile(const Layout &L, int64_t kt)
 // bytes of one tile's stream given its counts
 __host__ __device__ inline uint32_t tile_bytes(const Layout &L, int npanels, uint32_t nU, uint32_t nD)
 {
-    uint32_t b = uint32_t(npanels) * 2u * uint32_t(L.S) * 8u;
+    (void)npanels;
+    uint32_t b = uint32_t(kTilePanels) * 2u * uint32_t(L.S) * 8u;
     b += nD * uint32_t(L.B) * uint32_t(L.vb);
     b += nU * uint32_t(L.vb);
     b += (nU * uint32_t(L.B) + 7u) / 8u;
@@ -113,23 +118,40 @@ struct TileStreams {
 __device__ inline TileStreams tile_streams(int B, int vb, int npanels, uint32_t nU, uint32_t nD)
 {
     TileStreams t;
-    t.dense_off = uint32_t(npanels) * 2u * uint32_t(16 / B) * 8u;
+    (void)npanels;
+    t.dense_off = uint32_t(kTilePanels) * 2u * uint32_t(16 / B) * 8u;
     t.mag_off = t.dense_off + nD * uint32_t(B) * uint32_t(vb);
     t.sign_off = t.mag_off + nU * uint32_t(vb);
     return t;
 }
 
-// B-bit sign field of the UNIFIED block with payload index `rank`.
-template <int B>
-__device__ inline uint32_t load_sign_field(const uint8_t *signs, uint32_t rank)
+// bf16 storage with B = 16 keeps {magnitude, sign field} of a UNIFIED block in one 32-bit record.
+__host__ __device__ constexpr bool interleaved_records(int B, int vb) { return B == 16 && vb == 2; }
+
+// Magnitude bits and B-bit sign field of the UNIFIED block with payload index `rank`.
+// VB = value bytes (2: bf16 bits in the low half of q, 4: fp32 bits).
+template <int B, int VB>
+__device__ inline void load_unified(const uint8_t *tile, const TileStreams &ts, uint32_t rank, uint32_t &q,
+                                    uint32_t &s)
 {
-    if constexpr (B == 16) {
-        return reinterpret_cast<const uint16_t *>(signs)[rank];
-    } else if constexpr (B == 8) {
-        return signs[rank];
+    if constexpr (interleaved_records(B, VB)) {
+        const uint32_t rec = reinterpret_cast<const uint32_t *>(tile + ts.mag_off)[rank];
+        q = rec & 0xffffu;
+        s = rec >> 16;
     } else {
-        uint32_t bit = rank * B;
-        return (uint32_t(signs[bit >> 3]) >> (bit & 7u)) & ((1u << B) - 1u);
+        if constexpr (VB == 2)
+            q = reinterpret_cast<const uint16_t *>(tile + ts.mag_off)[rank];
+        else
+            q = reinterpret_cast<const uint32_t *>(tile + ts.mag_off)[rank];
+        const uint8_t *signs = tile + ts.sign_off;
+        if constexpr (B == 16) {
+            s = reinterpret_cast<const uint16_t *>(signs)[rank];
+        } else if constexpr (B == 8) {
+            s = signs[rank];
+        } else {
+            const uint32_t bit = rank * B;
+            s = (uint32_t(signs[bit >> 3]) >> (bit & 7u)) & ((1u << B) - 1u);
+        }
     }
 }
 
@@ -139,7 +161,7 @@ __device__ inline uint32_t load_sign_field(const uint8_t *signs, uint32_t rank)
 template <int B>
 __device__ inline void decode_block_bf16(uint32_t qbits, uint32_t sfield, uint32_t *out)
 {
-    const uint32_t qq = qbits | (qbits << 16);
+    const uint32_t qq = qbits | (qbits << 16);  // the stored magnitude is never negative: bit 15 is clear
     uint32_t sw;
     if constexpr (B == 16)
         sw = ((sfield & 0xffu) << 8) | ((sfield & 0xff00u) << 16);
@@ -150,7 +172,7 @@ __device__ inline void decode_block_bf16(uint32_t qbits, uint32_t sfield, uint32
     else
         sw = (sfield << 15) | (sfield << 30);
 #pragma unroll
-    for (int d = 0; d < B / 2; ++d) out[d] = (qq & 0x7fff7fffu) | ((sw << d) & 0x80008000u);
+    for (int d = 0; d < B / 2; ++d) out[d] = qq | ((sw << d) & 0x80008000u);
 }
 
 #endif  // __HIPCC__
