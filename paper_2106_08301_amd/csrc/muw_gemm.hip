@@ -202,6 +202,7 @@ muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, vo
         const size_t need = stream_gemm_workspace_bytes(L, a.M, a.blobs ? a.G : 1);
         if (need == 0 || (ws && ws_bytes >= need && !a.blobs)) return launch_stream_gemm(d, L, a, ws, st);
     }
+    if (tile_gemm_applicable(d, L, a)) return launch_tile_gemm(d, L, a, st);
     ActView av{};
     av.X = a.X;
     av.M = a.M;
