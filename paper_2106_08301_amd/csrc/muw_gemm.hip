@@ -222,17 +222,26 @@ muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, vo
                               st);
 }
 
-size_t conv2d_workspace_bytes(const muw_desc &, const Layout &, int64_t, int64_t, int64_t, int32_t,
+size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, int64_t H, int64_t W, int32_t,
                               int32_t)
 {
+    ConvArgs a{};
+    a.Nb = Nb;
+    a.H = H;
+    a.W = W;
+    a.OH = 1;
+    a.OW = 1;
+    if (d.wdtype == MUW_BF16 && d.Cin % 8 == 0 && tile_conv_applicable(d, L, a)) return tile_conv_workspace_bytes(d, a);
     return 0;
 }
 
-muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, void *, size_t,
+muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, void *ws, size_t ws_bytes,
                          hipStream_t st)
 {
     const int64_t M = a.Nb * a.OH * a.OW;
     if (M == 0) return MUW_OK;
+    if (tile_conv_applicable(d, L, a) && ws && ws_bytes >= tile_conv_workspace_bytes(d, a))
+        return launch_tile_conv(d, L, a, ws, st);
     ActView av{};
     av.X = a.X;
     av.M = M;

@@ -66,6 +66,11 @@ muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, 
 size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, int64_t H, int64_t W,
                               int32_t stride, int32_t pad);
 
+// muw_mfma.hip: convolution through the tile kernel (NHWC copy of the input in the workspace)
+bool tile_conv_applicable(const muw_desc &d, const Layout &L, const ConvArgs &a);
+size_t tile_conv_workspace_bytes(const muw_desc &d, const ConvArgs &a);
+muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &a, void *ws, hipStream_t st);
+
 inline muw_status hip_status(hipError_t e) { return e == hipSuccess ? MUW_OK : MUW_EHIP; }
 
 }  // namespace muw

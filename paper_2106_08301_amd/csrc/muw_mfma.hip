@@ -27,15 +27,37 @@ constexpr int kTN = 128;  // output columns (rows of W) per workgroup
 
 struct TileGemmArgs {
     const uint8_t *blob;
-    const uint16_t *X;
-    void *Y;
+    const uint16_t *X;  // linear: X[M][ldx]; convolution: the input as NHWC [Nb][H][W][Cin]
+    void *Y;            // linear: Y[M][ldy]; convolution: NCHW [Nb][N][OH][OW]
     int64_t M, ldx, ldy;
     int32_t ydtype;
+    // convolution geometry (CONV instantiation only); M = Nb*OH*OW, k = (kh*KW + kw)*Cin + cin
+    int32_t Cin, H, W, OH, OW, KW, stride, pad;
 };
 
 __device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
 
-template <int B, int TM>
+// NCHW -> NHWC copy of a bf16 tensor (64 channels x 64 pixels per workgroup through LDS), so that the
+// implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.
+__global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                      int C, int P)
+{
+    __shared__ uint16_t t[64][66];
+    const int64_t b = blockIdx.z;
+    const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i, p = p0 + tx;
+        t[i][tx] = (c < C && p < P) ? src[(b * C + c) * P + p] : uint16_t(0);
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int p = p0 + i, c = c0 + tx;
+        if (p < P && c < C) dst[(b * P + p) * C + c] = t[tx][i];
+    }
+}
+
+template <int B, int TM, bool CONV>
 __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layout L)
 {
     constexpr int MB = TM / 32;  // 16-row blocks per wave (two waves along M)
@@ -64,6 +86,22 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         for (int s = 0; s < 4; ++s) acc[mb][s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int arow = tid >> 3, achunk = tid & 7;  // A loader: rows arow + 32 i, one 16-byte chunk
+    // convolution: per loader row, the image's first pixel index and the top-left input coordinate
+    int32_t img0[CONV ? TM / 32 : 1], ihw0[CONV ? TM / 32 : 1];
+    if constexpr (CONV) {
+#pragma unroll
+        for (int i = 0; i < TM / 32; ++i) {
+            const int64_t m = m0 + arow + 32 * i;
+            img0[i] = -1;
+            ihw0[i] = 0;
+            if (m < a.M) {
+                const int pix = a.OH * a.OW;
+                const int b = int(m / pix), rem = int(m % pix), oh = rem / a.OW, ow = rem % a.OW;
+                img0[i] = b * a.H * a.W;
+                ihw0[i] = ((oh * a.stride - a.pad) << 16) | ((ow * a.stride - a.pad) & 0xffff);
+            }
+        }
+    }
 
     for (int64_t kp = 0; kp < L.KP; ++kp) {
         const int p = int(kp & 7);
@@ -71,11 +109,23 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         // ---- global loads of the A tile (issued first: longest latency)
         uint4 areg[TM / 32];
         const int64_t k = kp * kPanelK + achunk * 8;
+        if constexpr (CONV) {
+            const int tap = int(k / a.Cin), cin0 = int(k % a.Cin), kh = tap / a.KW, kw = tap % a.KW;
 #pragma unroll
-        for (int i = 0; i < TM / 32; ++i) {
-            const int64_t m = m0 + arow + 32 * i;
-            areg[i] = make_uint4(0, 0, 0, 0);
-            if (m < a.M && k + 8 <= L.K) areg[i] = *reinterpret_cast<const uint4 *>(a.X + m * a.ldx + k);
+            for (int i = 0; i < TM / 32; ++i) {
+                areg[i] = make_uint4(0, 0, 0, 0);
+                const int ih = (ihw0[i] >> 16) + kh, iw = int(int16_t(ihw0[i] & 0xffff)) + kw;
+                if (img0[i] >= 0 && k + 8 <= L.K && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
+                    areg[i] = *reinterpret_cast<const uint4 *>(
+                        a.X + (int64_t(img0[i]) + ih * a.W + iw) * a.Cin + cin0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM / 32; ++i) {
+                const int64_t m = m0 + arow + 32 * i;
+                areg[i] = make_uint4(0, 0, 0, 0);
+                if (m < a.M && k + 8 <= L.K) areg[i] = *reinterpret_cast<const uint4 *>(a.X + m * a.ldx + k);
+            }
         }
         // ---- decode this wave's two strip-panels into the B tile
 #pragma unroll
@@ -122,9 +172,30 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         for (int s = 0; s < 4; ++s) {
             const int64_t n = n0 + wn * 64 + s * 16 + r;
             if (n >= L.N) continue;
+            const int64_t mq = m0 + wm * (TM / 2) + mb * 16 + 4 * g;  // the lane's 4 consecutive rows
+            if constexpr (CONV) {
+                // NCHW: for a fixed output channel the 4 rows are 4 consecutive pixels
+                const int64_t pix = int64_t(a.OH) * a.OW;
+                if ((pix & 3) == 0 && mq + 3 < a.M && a.ydtype == MUW_F32) {
+                    const int64_t b = mq / pix, pp = mq % pix;
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(a.Y) + (b * L.N + n) * pix + pp) = acc[mb][s];
+                    continue;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t m = mq + v;
+                    if (m >= a.M) continue;
+                    const int64_t idx = ((m / pix) * L.N + n) * pix + m % pix;
+                    if (a.ydtype == MUW_F32)
+                        static_cast<float *>(a.Y)[idx] = acc[mb][s][v];
+                    else
+                        static_cast<uint16_t *>(a.Y)[idx] = f32_to_bf16_rne(acc[mb][s][v]);
+                }
+                continue;
+            }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int64_t m = m0 + wm * (TM / 2) + mb * 16 + 4 * g + v;
+                const int64_t m = mq + v;
                 if (m >= a.M) continue;
                 if (a.ydtype == MUW_F32)
                     static_cast<float *>(a.Y)[m * a.ldy + n] = acc[mb][s][v];
@@ -134,16 +205,16 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         }
 }
 
-template <int B>
+template <int B, bool CONV>
 muw_status launch_tile_b(const TileGemmArgs &a, const Layout &L, hipStream_t st)
 {
     const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
     if (a.M > 128) {
         dim3 grid(nt, unsigned((a.M + 255) / 256));
-        k_tile_gemm_bf16<B, 256><<<grid, 256, 0, st>>>(a, L);
+        k_tile_gemm_bf16<B, 256, CONV><<<grid, 256, 0, st>>>(a, L);
     } else {
         dim3 grid(nt, unsigned((a.M + 127) / 128));
-        k_tile_gemm_bf16<B, 128><<<grid, 256, 0, st>>>(a, L);
+        k_tile_gemm_bf16<B, 128, CONV><<<grid, 256, 0, st>>>(a, L);
     }
     return hip_status(hipGetLastError());
 }
@@ -160,12 +231,60 @@ bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 
 muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &g, hipStream_t st)
 {
-    TileGemmArgs a{static_cast<const uint8_t *>(g.blob), static_cast<const uint16_t *>(g.X), g.Y, g.M, g.ldx,
-                   g.ldy, g.ydtype};
+    TileGemmArgs a{};
+    a.blob = static_cast<const uint8_t *>(g.blob);
+    a.X = static_cast<const uint16_t *>(g.X);
+    a.Y = g.Y;
+    a.M = g.M;
+    a.ldx = g.ldx;
+    a.ldy = g.ldy;
+    a.ydtype = g.ydtype;
     switch (d.B) {
-    case 4: return launch_tile_b<4>(a, L, st);
-    case 8: return launch_tile_b<8>(a, L, st);
-    case 16: return launch_tile_b<16>(a, L, st);
+    case 4: return launch_tile_b<4, false>(a, L, st);
+    case 8: return launch_tile_b<8, false>(a, L, st);
+    case 16: return launch_tile_b<16, false>(a, L, st);
+    default: return MUW_EUNSUPPORTED;
+    }
+}
+
+// Convolution through the tile kernel: bf16, Cin a multiple of 8, sizes that fit 32-bit pixel indices.
+bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
+{
+    if (d.wdtype != MUW_BF16 || d.Cin % 8 != 0) return false;
+    if (a.Nb * a.H * a.W >= (int64_t(1) << 31) || a.H >= 32768 || a.W >= 32768) return false;
+    if (a.Nb > 65535 || (a.Nb * a.OH * a.OW + 127) / 128 > 65535) return false;
+    if ((reinterpret_cast<uintptr_t>(a.X) & 1u)) return false;
+    return true;
+}
+
+size_t tile_conv_workspace_bytes(const muw_desc &d, const ConvArgs &a)
+{
+    return size_t(a.Nb) * size_t(a.H) * size_t(a.W) * size_t(d.Cin) * 2u;
+}
+
+muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &c, void *ws, hipStream_t st)
+{
+    const int P = int(c.H * c.W);
+    dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
+    k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin, P);
+    TileGemmArgs a{};
+    a.blob = static_cast<const uint8_t *>(c.blob);
+    a.X = static_cast<const uint16_t *>(ws);
+    a.Y = c.Y;
+    a.M = c.Nb * c.OH * c.OW;
+    a.ydtype = c.ydtype;
+    a.Cin = d.Cin;
+    a.H = int32_t(c.H);
+    a.W = int32_t(c.W);
+    a.OH = int32_t(c.OH);
+    a.OW = int32_t(c.OW);
+    a.KW = d.KW;
+    a.stride = c.stride;
+    a.pad = c.pad;
+    switch (d.B) {
+    case 4: return launch_tile_b<4, true>(a, L, st);
+    case 8: return launch_tile_b<8, true>(a, L, st);
+    case 16: return launch_tile_b<16, true>(a, L, st);
     default: return MUW_EUNSUPPORTED;
     }
 }
