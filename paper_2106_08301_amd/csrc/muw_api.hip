@@ -30,7 +30,7 @@ Layout layout_of(const muw_desc *d) { return make_layout(d->N, d->K, d->B, value
 size_t blob_upper_bound(const Layout &L, int64_t n_u, int64_t n_d)
 {
     uint64_t b = L.streams_off;
-    b += uint64_t(L.NT) * uint64_t(kTilePanels) * 2u * uint64_t(L.S) * 8u;  // masks (8 panels per tile)
+    b += uint64_t(L.NT) * uint64_t(kTilePanels) * 2u * uint64_t(L.S) * 8u;  // masks (every tile has the full mask area)
     b += uint64_t(n_d) * uint64_t(L.B) * uint64_t(L.vb);             // dense payload
     b += uint64_t(n_u) * uint64_t(L.vb);                             // magnitudes
     b += (uint64_t(n_u) * uint64_t(L.B) + 7) / 8;                    // sign bits

@@ -3,7 +3,7 @@
 // Geometry (chosen for 64-wide wavefronts and the 16x16x32 bf16 MFMA):
 //   strip  = 16 consecutive output rows n
 //   panel  = one strip x 64 consecutive k             (two 16x16x32 MFMA B-operands)
-//   tile   = one strip x 512 consecutive k = up to 8 panels; the unit that owns payload streams
+//   tile   = one strip x 256 consecutive k = up to 4 panels; the unit that owns payload streams
 // Inside a panel, lane l = (r = l % 16, g = l / 16) owns row r and the 16 weights k = 16 g .. 16 g + 15
 // of the panel, i.e. S = 16 / B whole blocks ("sub-steps" j = 0 .. S-1, block column S*g + j of the
 // panel).  MFMA h (h = 0, 1) of the panel takes the lane's weights 8 h .. 8 h + 7, so the matching
@@ -12,7 +12,7 @@
 // A tile's byte stream (16-byte aligned, padded to 16 bytes):
 //   masks   per panel: U[0..S-1] then D[0..S-1], 64-bit each; bit l of U[j] / D[j] says that lane l's
 //           block j is UNIFIED / DENSE.  Neither bit: PRUNED (or outside the matrix).  2 bits per block.
-//           The mask area always spans 8 panels (a ragged last tile has zero masks for the panels it
+//           The mask area always spans 4 panels (a ragged last tile has zero masks for the panels it
 //           lacks), so payload offsets do not depend on the tile's position.
 //   dense   the B values of each DENSE block, in (panel, sub-step, lane) order
 //   mags    one stored magnitude per UNIFIED block, same order
@@ -34,7 +34,7 @@ namespace muw {
 
 constexpr int kStripRows = 16;
 constexpr int kPanelK = 64;
-constexpr int kTilePanels = 8;
+constexpr int kTilePanels = 4;
 constexpr int kTileK = kPanelK * kTilePanels;
 constexpr uint32_t kMagic = 0x3157554du;  // "MUW1"
 constexpr size_t kHeaderBytes = 64;

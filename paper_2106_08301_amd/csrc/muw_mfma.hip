@@ -104,8 +104,8 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
     }
 
     for (int64_t kp = 0; kp < L.KP; ++kp) {
-        const int p = int(kp & 7);
-        const int64_t kt = kp >> 3;
+        const int p = int(kp % kTilePanels);
+        const int64_t kt = kp / kTilePanels;
         // ---- global loads of the A tile (issued first: longest latency)
         uint4 areg[TM / 32];
         const int64_t k = kp * kPanelK + achunk * 8;

@@ -2,20 +2,21 @@
 // time is the time to stream the compressed weights from HBM once (paper Sec. 3.2: the stored form of
 // a pruned block is nothing, of a unified block one magnitude and B sign bits).
 //
-// One persistent workgroup of 8 wavefronts per compute unit.  Wave w keeps the activations of tile
-// column kt = 8 c + w (512 consecutive k, all M <= 16 rows) in registers as MFMA A-operands for as
-// long as the workgroup stays on one weight matrix, and walks down the strips (16 output rows) of
-// that tile column:
+// One persistent workgroup of 16 wavefronts per compute unit (4 per SIMD: the kernel is bound by
+// instruction issue, so it needs the thread-level parallelism).  Wave w keeps the activations of tile
+// column kt = 16 c + w (256 consecutive k, all M <= 16 rows: 32 VGPRs of MFMA A-operands) in registers
+// for as long as the workgroup stays on one weight matrix, and walks down the strips (16 output rows)
+// of that tile column:
 //   - the tile's byte stream goes HBM -> LDS with global_load_lds_dwordx4 (no registers, no VALU),
-//     D tiles ahead of the one being decoded, into a per-wave ring of D+1 slots;
-//   - the lane decodes its 16 weights of each panel from LDS (mask -> payload index by v_mbcnt,
-//     magnitude | sign bits -> bf16 pairs with one shift and one bit-select per dword; pruned blocks
-//     read no payload) straight into the B-operand of two 16x16x32 bf16 MFMAs;
-//   - after SPI strips the 8 partial 16x16 accumulators of a strip (one per tile column) are summed
-//     through LDS by one wave (the role rotates) and written to Y.  No atomics: results are
-//     bitwise reproducible.
+//     D tiles ahead of the one being decoded, into a per-wave ring of D + 1 slots;
+//   - masks are read from the LDS copy one tile ahead and made scalar (v_readfirstlane); the lane
+//     finds its payload by v_mbcnt, reads it from LDS (pruned blocks read nothing) and turns
+//     magnitude | sign bits into bf16 pairs with one shift and one bit-select per dword, straight into
+//     the B-operand of two 16x16x32 bf16 MFMAs per panel;
+//   - the 16 partial 16x16 accumulators of a strip (one per tile column) are summed through LDS by one
+//     wave (the role rotates) and written to Y.  No atomics: results are bitwise reproducible.
 // Every tile issues exactly NCH 1-KiB DMA instructions (lanes past the end of the stream re-read its
-// last 16 bytes), so "tile q has landed" is the static wait vmcnt(D * NCH).
+// last 16 bytes), so "tiles q and q + 1 have landed" is the static wait vmcnt((D - 1) * NCH).
 #include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
@@ -25,8 +26,20 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
+// Explicit address spaces: a pointer read from a device pointer table is "generic" to the compiler,
+// and generic (flat) accesses count in both memory counters and force full drains.
+typedef __attribute__((address_space(1))) const u32x4_t g_cu32x4;
+typedef __attribute__((address_space(1))) const uint32_t g_cu32;
+typedef __attribute__((address_space(1))) float g_float;
+typedef __attribute__((address_space(1))) uint16_t g_u16;
+typedef const __attribute__((address_space(4))) uint64_t c_u64;
+
+constexpr int kWaves = 16;       // wavefronts per workgroup = tile columns handled at once
+constexpr int kP = kTilePanels;  // panels per tile (4)
+static_assert(kP == 4, "the streaming kernel is written for 4-panel tiles");
 
 struct StreamArgs {
     const uint8_t *blob;
@@ -36,33 +49,26 @@ struct StreamArgs {
     const void *const *Xs;
     void *const *Ys;
     int32_t G, M;
-    int64_t ldx, ldy;
+    int32_t ldx, ldy;  // row strides in elements (M <= 16 rows: 32-bit offsets suffice)
     int32_t ydtype;
-    int32_t nbpm;      // batches (of SPI strips) per matrix
-    int32_t nbatches;  // G * nbpm
-    int32_t per_wg;    // batches per workgroup
-    float *Ypart;      // [nchunk][G][M][N] partial sums when K is split over blockIdx.y, else null
+    int32_t nstrips;  // G * NS: strips over all matrices
+    int32_t per_wg;   // strips per workgroup
+    float *Ypart;     // [nchunk][G][M][N] partial sums when K is split over blockIdx.y, else null
     int32_t nchunk;
 };
 
-// Explicit address spaces: a pointer read from a device pointer table is "generic" to the compiler,
-// and generic (flat) accesses count in both memory counters and force full drains.
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(1))) const u32x4_t g_cu32x4;
-typedef __attribute__((address_space(1))) const uint32_t g_cu32;
-typedef __attribute__((address_space(1))) float g_float;
-typedef __attribute__((address_space(1))) uint16_t g_u16;
-typedef const __attribute__((address_space(4))) uint64_t c_u64;
+// The few layout numbers the kernel needs (32-bit, to keep scalar registers free).
+struct StreamGeom {
+    uint32_t dir_off, streams_off;
+    int32_t KT, NS, N, K;
+};
 
 // Entry i of a device table of pointers, through the scalar cache (i is wave-uniform).
 __device__ inline uint64_t table_entry(const void *table, int i) { return ((c_u64 *)table)[i]; }
 
 // Workgroup barrier for LDS traffic only: waits for this wave's LDS operations, not for the DMA
 // prefetches in flight (a full __syncthreads() drains vmcnt as well).
-__device__ inline void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int N>
 __device__ inline void wait_vmcnt()
@@ -72,70 +78,12 @@ __device__ inline void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
 }
 
-__device__ inline uint64_t uniform64(uint64_t v)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
-    return (uint64_t(hi) << 32) | lo;
-}
-
-// ---- B < 16: masks are read from the LDS copy of the tile and made wave-uniform ------------------
-template <int B>
-__device__ inline void decode_panel_lds(const uint8_t *tile, const TileStreams &ts, int p, uint32_t &ru,
-                                        uint32_t &rd, uint32_t *w)
-{
-    constexpr int S = 16 / B;
-    const uint64_t *masks = reinterpret_cast<const uint64_t *>(tile) + p * 2 * S;
-#pragma unroll
-    for (int j = 0; j < S; ++j) {
-        const uint64_t mu = uniform64(masks[j]), md = uniform64(masks[S + j]);
-        const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
-        ru += __popcll(mu);
-        rd += __popcll(md);
-        uint32_t q = 0, s = 0;
-        if (__builtin_amdgcn_inverse_ballot_w64(mu)) load_unified<B, 2>(tile, ts, rku, q, s);
-        decode_block_bf16<B>(q, s, w + j * (B / 2));
-        if (__builtin_amdgcn_inverse_ballot_w64(md)) {
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(tile + ts.dense_off) + rkd * (B / 2);
-#pragma unroll
-            for (int d = 0; d < B / 2; ++d) w[j * (B / 2) + d] = src[d];
-        }
-    }
-}
-
-template <int B>
-__device__ inline void process_tile_generic(const uint8_t *tile, int np, int npq, uint32_t nU, uint32_t nD,
-                                            const uint4 (&xr)[8][2], f32x4 &acc0, f32x4 &acc1)
-{
-    const TileStreams ts = tile_streams(B, 2, np, nU, nD);
-    uint32_t ru = 0, rd = 0;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        if (p < npq) {
-            uint32_t w[8];
-            decode_panel_lds<B>(tile, ts, p, ru, rd, w);
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, xr[p][0]),
-                __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3])), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, xr[p][1]),
-                __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7])), acc1, 0, 0, 0);
-        }
-    }
-}
-
-// ---- B = 16: a half tile (4 panels) at a time.  Its 8 masks are read from the LDS copy of the tile
-// (uniform address) together with the previous half's payload reads, then made scalar; all payload
-// reads of a half are issued before its first decode ------------------------------------------------
-struct HalfMasks {
-    uint64_t u[4], d[4];
-};
-
 // LDS reads of DMA-filled memory are written as inline assembly on purpose: for an ordinary LDS
 // load that may alias a pending global_load_lds the compiler inserts a wait for ALL pending DMA,
 // which would cancel the prefetch distance.  Here the slot discipline (a slot is read only after the
 // explicit vmcnt wait for its own DMA, and refilled only after its last read has returned) is the
-// proof of ordering, and the reads are followed by one explicit lgkmcnt(0).
+// proof of ordering, and every batch of reads is followed by one explicit lgkmcnt(0) whose operands
+// tie it to the registers it guards.
 __device__ inline uint32_t lds_offset(const void *p)
 {
     return uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint8_t *)p));
@@ -146,17 +94,53 @@ __device__ inline uint32_t lds_read_b32(uint32_t addr)
     asm volatile("ds_read_b32 %0, %1" : "=v"(dst) : "v"(addr));
     return dst;
 }
+__device__ inline uint32_t lds_read_u16(uint32_t addr)
+{
+    uint32_t dst;
+    asm volatile("ds_read_u16 %0, %1" : "=v"(dst) : "v"(addr));
+    return dst;
+}
+__device__ inline uint32_t lds_read_u8(uint32_t addr)
+{
+    uint32_t dst;
+    asm volatile("ds_read_u8 %0, %1" : "=v"(dst) : "v"(addr));
+    return dst;
+}
 __device__ inline void lds_read_2xb128(u32x4_t &lo, u32x4_t &hi, uint32_t addr)
 {
     asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16" : "=&v"(lo), "=&v"(hi) : "v"(addr));
 }
+__device__ inline u32x4_t lds_read_b128(uint32_t addr)
+{
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+__device__ inline uint64_t lds_read_b64(uint32_t addr)
+{
+    uint64_t v;
+    asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
 
-// Four 16-byte {U, D} mask pairs, as read from LDS (identical in every lane).
-struct RawMasks {
-    u32x4_t v[4];
+__device__ inline uint64_t uniform64(uint64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+    return (uint64_t(hi) << 32) | lo;
+}
+
+// ------------------------------------------------------------------------------------------------
+// B = 16: the tile's 8 masks (4 panels x {U, D}) are 64 bytes, read from LDS one tile ahead.
+// ------------------------------------------------------------------------------------------------
+struct TileMasks16 {
+    uint64_t u[kP], d[kP];
+};
+struct RawMasks16 {
+    u32x4_t v[kP];  // {U lo, U hi, D lo, D hi} of one panel, identical in every lane
 };
 
-__device__ inline void lds_read_masks(RawMasks &mv, uint32_t addr)
+__device__ inline void lds_read_masks16(RawMasks16 &mv, uint32_t addr)
 {
     asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\t"
                  "ds_read_b128 %2, %4 offset:32\n\tds_read_b128 %3, %4 offset:48"
@@ -164,33 +148,31 @@ __device__ inline void lds_read_masks(RawMasks &mv, uint32_t addr)
                  : "v"(addr));
 }
 
-// The four raw mask pairs into scalar registers.
-__device__ inline void scalar_masks(const RawMasks &mv, HalfMasks &m)
+__device__ inline void scalar_masks16(const RawMasks16 &mv, TileMasks16 &m)
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kP; ++i) {
         // (the builtin returns a signed int: go through uint32_t before widening)
         const uint32_t ulo = __builtin_amdgcn_readfirstlane(mv.v[i].x), uhi = __builtin_amdgcn_readfirstlane(mv.v[i].y);
         const uint32_t dlo = __builtin_amdgcn_readfirstlane(mv.v[i].z), dhi = __builtin_amdgcn_readfirstlane(mv.v[i].w);
-        const uint64_t u = (uint64_t(uhi) << 32) | ulo;
-        const uint64_t d = (uint64_t(dhi) << 32) | dlo;
-        m.u[i] = u;
-        m.d[i] = d;
+        m.u[i] = (uint64_t(uhi) << 32) | ulo;
+        m.d[i] = (uint64_t(dhi) << 32) | dlo;
     }
 }
 
-// Decode + MFMA of panels P0 .. P0 + 3; also fetches the raw masks at next_masks (LDS address) for the
-// half that follows, so that they arrive under the same wait as this half's payload.
-template <int P0>
-__device__ inline void process_half16(uint32_t tile_lds, const HalfMasks &m, uint32_t dense_off,
-                                      uint32_t rec_off, uint32_t &ru, uint32_t &rd, const uint4 (&xr)[8][2],
-                                      f32x4 &acc0, f32x4 &acc1, uint32_t next_masks, RawMasks &mv)
+// One tile (4 panels) of a B = 16 layer: issue every payload read (and the raw masks of the next
+// tile), wait once, then decode and feed 8 MFMAs.
+__device__ inline void process_tile16(uint32_t tile_lds, const TileMasks16 &m, uint32_t nD, const uint4 (&xr)[kP][2],
+                                      f32x4 &acc0, f32x4 &acc1, uint32_t next_tile_lds, RawMasks16 &mv)
 {
-    uint32_t rec[4];
-    u32x4_t wlo[4], whi[4];
-    lds_read_masks(mv, next_masks);
+    constexpr uint32_t dense_off = kP * 16u;
+    const uint32_t rec_off = dense_off + nD * 32u;
+    uint32_t rec[kP];
+    u32x4_t wlo[kP], whi[kP];
+    uint32_t ru = 0, rd = 0;
+    lds_read_masks16(mv, next_tile_lds);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < kP; ++p) {
         // Every lane reads (a lane without a UNIFIED block reads its neighbour's record and drops it
         // below): an unconditional read leaves no register copy between the read and the wait.
         rec[p] = lds_read_b32(tile_lds + rec_off + 4u * (ru + mbcnt64(m.u[p])));
@@ -204,7 +186,7 @@ __device__ inline void process_half16(uint32_t tile_lds, const HalfMasks &m, uin
                    "+v"(wlo[2]), "+v"(wlo[3]), "+v"(whi[0]), "+v"(whi[1]), "+v"(whi[2]), "+v"(whi[3]),
                    "+v"(mv.v[0]), "+v"(mv.v[1]), "+v"(mv.v[2]), "+v"(mv.v[3]));
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < kP; ++p) {
         if (!__builtin_amdgcn_inverse_ballot_w64(m.d[p])) {
             // record = magnitude (low half, sign bit clear) | permuted sign field (high half)
             const uint32_t rc = __builtin_amdgcn_inverse_ballot_w64(m.u[p]) ? rec[p] : 0u;
@@ -219,86 +201,130 @@ __device__ inline void process_half16(uint32_t tile_lds, const HalfMasks &m, uin
             whi[p].z = qq | ((sw << 6) & 0x80008000u);
             whi[p].w = qq | ((sw << 7) & 0x80008000u);
         }
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[P0 + p][0]),
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][0]),
                                                        __builtin_bit_cast(bf16x8, wlo[p]), acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[P0 + p][1]),
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][1]),
                                                        __builtin_bit_cast(bf16x8, whi[p]), acc1, 0, 0, 0);
     }
 }
 
-// The few layout numbers the kernel needs (32-bit, to keep scalar registers for the masks).
-struct StreamGeom {
-    uint32_t dir_off, streams_off;
-    int32_t KT, NS, N, K;
-};
+// ------------------------------------------------------------------------------------------------
+// B = 4, 8: same walk, panel by panel, masks read from LDS when needed (not tuned: these block
+// lengths are not on the memory-bound benchmark).
+// ------------------------------------------------------------------------------------------------
+template <int B>
+__device__ inline void process_tile_small_b(uint32_t tile_lds, uint32_t nU, uint32_t nD, const uint4 (&xr)[kP][2],
+                                            f32x4 &acc0, f32x4 &acc1)
+{
+    constexpr int S = 16 / B;
+    constexpr uint32_t dense_off = kP * 2u * S * 8u;
+    const uint32_t mag_off = dense_off + nD * uint32_t(B) * 2u, sign_off = mag_off + nU * 2u;
+    uint32_t ru = 0, rd = 0;
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+        uint32_t w[8];
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            uint64_t mu_v = lds_read_b64(tile_lds + uint32_t(p * 2 * S + j) * 8u);
+            uint64_t md_v = lds_read_b64(tile_lds + uint32_t(p * 2 * S + S + j) * 8u);
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(mu_v), "+v"(md_v));
+            const uint64_t mu = uniform64(mu_v), md = uniform64(md_v);
+            const uint32_t rku = ru + mbcnt64(mu), rkd = rd + mbcnt64(md);
+            ru += __popcll(mu);
+            rd += __popcll(md);
+            uint32_t q = lds_read_u16(tile_lds + mag_off + 2u * rku);
+            const uint32_t bit = rku * B;
+            uint32_t s = lds_read_u8(tile_lds + sign_off + (bit >> 3));
+            u32x4_t dn = {0, 0, 0, 0};
+            if (__builtin_amdgcn_inverse_ballot_w64(md)) {
+                if constexpr (B == 8) {
+                    dn = lds_read_b128(tile_lds + dense_off + 16u * rkd);
+                } else {
+                    const uint64_t t = lds_read_b64(tile_lds + dense_off + 8u * rkd);
+                    dn.x = uint32_t(t);
+                    dn.y = uint32_t(t >> 32);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q), "+v"(s), "+v"(dn));
+            s = (s >> (bit & 7u)) & ((1u << B) - 1u);
+            if (!__builtin_amdgcn_inverse_ballot_w64(mu)) {
+                q = 0;
+                s = 0;
+            }
+            decode_block_bf16<B>(q, s, w + j * (B / 2));
+            if (__builtin_amdgcn_inverse_ballot_w64(md)) {
+                w[j * (B / 2)] = dn.x;
+                w[j * (B / 2) + 1] = dn.y;
+                if constexpr (B == 8) {
+                    w[j * (B / 2) + 2] = dn.z;
+                    w[j * (B / 2) + 3] = dn.w;
+                }
+            }
+        }
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, xr[p][0]), __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3])),
+            acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+            __builtin_bit_cast(bf16x8, xr[p][1]), __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7])),
+            acc1, 0, 0, 0);
+    }
+}
 
-template <int B, int NCH, int D, int SPI>
-__global__ __launch_bounds__(512) void k_stream_bf16(StreamArgs a, StreamGeom L)
+template <int B, int NCH, int D>
+__global__ __launch_bounds__(kWaves * 64) void k_stream_bf16(StreamArgs a, StreamGeom L)
 {
     constexpr int SLOT = NCH * 1024;
     constexpr int NSLOT = D + 1;
-    __shared__ __attribute__((aligned(16))) uint8_t ring[8][NSLOT * SLOT];
-    __shared__ __attribute__((aligned(16))) float red[2][8][SPI][64][4];
+    __shared__ __attribute__((aligned(16))) uint8_t ring[kWaves][NSLOT * SLOT];
+    __shared__ __attribute__((aligned(16))) float red[2][kWaves][64][4];
 
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63, r = lane & 15, g4 = lane >> 4;
     const int chunk = blockIdx.y;
-    const int kt = chunk * 8 + wave;
+    const int kt = chunk * kWaves + wave;
     const bool active = kt < L.KT;
-    int np = 0;
-    if (active) {
-        const int left = (L.K + kPanelK - 1) / kPanelK - kt * kTilePanels;
-        np = left < kTilePanels ? left : kTilePanels;
-    }
 
-    const int bb_lo = blockIdx.x * a.per_wg;
-    int bb_hi = bb_lo + a.per_wg;
-    if (bb_hi > a.nbatches) bb_hi = a.nbatches;
-    if (bb_lo >= bb_hi) return;
-    const int nb = bb_hi - bb_lo;
-    const int nseq = nb * SPI;
+    const int s_lo = blockIdx.x * a.per_wg;
+    int s_hi = s_lo + a.per_wg;
+    if (s_hi > a.nstrips) s_hi = a.nstrips;
+    if (s_lo >= s_hi) return;
+    const int nseq = s_hi - s_lo;  // this workgroup's strips, over all matrices: element q = strip s_lo + q
     uint8_t *myring = ring[wave];
 
     // ---- directory window: lane l holds stream address, size and counts of sequence element qbase + l
     int qbase = 0;
     uint64_t q_addr = 0;
-    uint32_t q_bytes = 0, q_cnt = 0, q_np = 0;
+    uint32_t q_bytes = 0, q_cnt = 0;
     auto refill = [&](int base) {
         qbase = base;
         const int qq = base + lane;
-        const int bb = bb_lo + qq / SPI;
-        const int gi = bb / a.nbpm;
-        const int64_t strip = int64_t(bb % a.nbpm) * SPI + qq % SPI;
-        const bool ok = active && qq < nseq && strip < L.NS;
+        const int gs = s_lo + qq;
+        const int gi = gs / L.NS;
+        const int64_t strip = gs % L.NS;
+        const bool ok = active && qq < nseq;
         uint64_t blob = reinterpret_cast<uint64_t>(a.blob);
         if (a.blobs) blob = ((const __attribute__((address_space(1))) uint64_t *)a.blobs)[ok ? gi : 0];
         q_addr = blob;  // a valid 16 bytes for elements with nothing to fetch
         q_bytes = 16;
         q_cnt = 0;
-        q_np = 0;
         if (ok) {
             g_cu32 *de = (g_cu32 *)(blob + L.dir_off + uint64_t(strip * L.KT + kt) * sizeof(DirEntry));
             const uint32_t off16 = de[0], cnt = de[1], next = de[2];
             q_addr = blob + L.streams_off + uint64_t(off16) * 16;
             q_bytes = (next - off16) * 16;
             q_cnt = cnt;  // nU | nD << 16
-            q_np = uint32_t(np);
         }
         // Drain on every path: a load left pending here would turn each later read of the window
         // registers into a wait for all DMA prefetches as well.
         wait_vmcnt<0>();
     };
-    auto entry_addr = [&](int e) {
-        const uint32_t lo = __builtin_amdgcn_readlane(uint32_t(q_addr), e - qbase);
-        const uint32_t hi = __builtin_amdgcn_readlane(uint32_t(q_addr >> 32), e - qbase);
-        return (uint64_t(hi) << 32) | lo;
-    };
     // ---- issue the NCH DMA instructions of sequence element qi into its ring slot
     auto issue = [&](int qi) {
-        const uint64_t base = entry_addr(qi);
-        const uint32_t bytes = __builtin_amdgcn_readlane(q_bytes, qi - qbase);
+        const uint32_t alo = __builtin_amdgcn_readlane(uint32_t(q_addr), qi - qbase);
+        const uint32_t ahi = __builtin_amdgcn_readlane(uint32_t(q_addr >> 32), qi - qbase);
+        const uint64_t base = (uint64_t(ahi) << 32) | alo;
+        const uint32_t last = __builtin_amdgcn_readlane(q_bytes, qi - qbase) - 16;
         const int slot = qi % NSLOT;
-        const uint32_t last = bytes - 16;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             uint32_t off = uint32_t(c) * 1024u + uint32_t(lane) * 16u;
@@ -308,37 +334,48 @@ __global__ __launch_bounds__(512) void k_stream_bf16(StreamArgs a, StreamGeom L)
         }
     };
 
-    uint4 xr[8][2];
+    uint4 xr[kP][2];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) xr[p][0] = xr[p][1] = make_uint4(0, 0, 0, 0);
+    for (int p = 0; p < kP; ++p) xr[p][0] = xr[p][1] = make_uint4(0, 0, 0, 0);
     int cur_g = -1;
-    RawMasks mv{};  // raw masks of the half that is decoded next
+    uint64_t Ycur = 0;  // output matrix of the current weight matrix (kept in scalar registers)
+    RawMasks16 mv{};  // B = 16: raw masks of the tile that is decoded next
 
     if (active) {
         refill(0);
         for (int qi = 0; qi < D && qi < nseq; ++qi) issue(qi);
         if constexpr (B == 16) {
             wait_vmcnt<0>();  // once per workgroup: tile 0 must have landed before its masks are read
-            lds_read_masks(mv, lds_offset(myring));
+            lds_read_masks16(mv, lds_offset(myring));
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(mv.v[0]), "+v"(mv.v[1]), "+v"(mv.v[2]), "+v"(mv.v[3]));
         }
     }
 
-    for (int bi = 0; bi < nb; ++bi) {
-        const int bb = bb_lo + bi;
-        const int gi = bb / a.nbpm;
-        const int64_t strip0 = int64_t(bb % a.nbpm) * SPI;
-        if (gi != cur_g && active) {
+    int gi = s_lo / L.NS, strip = s_lo % L.NS - 1;  // matrix and strip of element q, stepped without dividing
+    for (int q = 0; q < nseq; ++q) {
+        if (++strip == L.NS) {
+            strip = 0;
+            ++gi;
+        }
+        const bool new_matrix = gi != cur_g;
+        if (new_matrix) {
             cur_g = gi;
+            Ycur = a.Ys ? table_entry(a.Ys, gi) : reinterpret_cast<uint64_t>(a.Y);
+        }
+        if (new_matrix && active) {
             const uint64_t X = a.Xs ? table_entry(a.Xs, gi) : reinterpret_cast<uint64_t>(a.X);
+            // (opaque copies: keep the address arithmetic of this rare path out of the loop-invariant
+            // registers the compiler would otherwise spill to scratch)
+            int ldx = a.ldx;
+            asm volatile("" : "+s"(ldx));
 #pragma unroll
-            for (int p = 0; p < 8; ++p)
+            for (int p = 0; p < kP; ++p)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const int64_t k = int64_t(kt) * kTileK + p * kPanelK + 16 * g4 + 8 * h;
+                    const int k = kt * kTileK + p * kPanelK + 16 * g4 + 8 * h;
                     uint4 v = make_uint4(0, 0, 0, 0);
                     if (r < a.M && k + 8 <= L.K) {
-                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(int64_t(r) * a.ldx + k) * 2u);
+                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
                         v = make_uint4(t.x, t.y, t.z, t.w);
                     }
                     xr[p][h] = v;
@@ -347,68 +384,62 @@ __global__ __launch_bounds__(512) void k_stream_bf16(StreamArgs a, StreamGeom L)
             // wait for the DMA prefetches in flight.
             wait_vmcnt<0>();
         }
-#pragma unroll
-        for (int s = 0; s < SPI; ++s) {
-            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-            if (active) {
-                const int q = bi * SPI + s;
-                const int qi = q + D;
-                if (qi < nseq && qi >= qbase + 64) refill(q);  // keeps q .. q + 63, covers q, q + 1, q + D
-                const uint32_t cnt = __builtin_amdgcn_readlane(q_cnt, q - qbase);
-                const int npq = int(__builtin_amdgcn_readlane(q_np, q - qbase));
-                // After this wait tiles q and q + 1 have landed (q + 1 because its first masks are
-                // fetched while q is still being decoded).
-                if (qi < nseq) {
-                    issue(qi);
-                    wait_vmcnt<(D - 1) * NCH>();
-                } else {
-                    wait_vmcnt<0>();
-                }
-                const uint8_t *tile = myring + (q % NSLOT) * SLOT;
-                if constexpr (B == 16) {
-                    const uint32_t dense_off = 128u, rec_off = dense_off + (cnt >> 16) * 32u;
-                    uint32_t ru = 0, rd = 0;
-                    const uint32_t tl = lds_offset(tile);
-                    const uint32_t tl_next = lds_offset(myring + ((q + 1) % NSLOT) * SLOT);
-                    HalfMasks sm;
-                    scalar_masks(mv, sm);
-                    process_half16<0>(tl, sm, dense_off, rec_off, ru, rd, xr, acc0, acc1, tl + 64u, mv);
-                    scalar_masks(mv, sm);
-                    process_half16<4>(tl, sm, dense_off, rec_off, ru, rd, xr, acc0, acc1, tl_next, mv);
-                } else
-                    process_tile_generic<B>(tile, np, npq, cnt & 0xffffu, cnt >> 16, xr, acc0, acc1);
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        if (active) {
+            const int qi = q + D;
+            if (qi < nseq && qi >= qbase + 64) refill(q);  // keeps q .. q + 63: covers q, q + 1, q + D
+            const uint32_t cnt = __builtin_amdgcn_readlane(q_cnt, q - qbase);
+            // After this wait tiles q and q + 1 have landed (q + 1 because its masks are fetched while
+            // q is being decoded).
+            if (qi < nseq) {
+                issue(qi);
+                wait_vmcnt<(D - 1) * NCH>();
+            } else {
+                wait_vmcnt<0>();
             }
-            *reinterpret_cast<f32x4 *>(red[bi & 1][wave][s][lane]) = acc0 + acc1;
+            const uint32_t tl = lds_offset(myring + (q % NSLOT) * SLOT);
+            if constexpr (B == 16) {
+                TileMasks16 sm;
+                scalar_masks16(mv, sm);
+                process_tile16(tl, sm, cnt >> 16, xr, acc0, acc1, lds_offset(myring + ((q + 1) % NSLOT) * SLOT), mv);
+            } else {
+                process_tile_small_b<B>(tl, cnt & 0xffffu, cnt >> 16, xr, acc0, acc1);
+            }
         }
+        *reinterpret_cast<f32x4 *>(red[q & 1][wave][lane]) = acc0 + acc1;
         lds_barrier();
-        if (wave == (bi & 7)) {
-            const uint64_t Y = a.Ys ? table_entry(a.Ys, gi) : reinterpret_cast<uint64_t>(a.Y);
+        if (wave == (q & (kWaves - 1))) {
+            const uint64_t Y = Ycur;
+            // (asm reads for the same reason as the tile reads: no wait on the DMA in flight)
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};  // waves without a tile column wrote zeros
 #pragma unroll
-            for (int s = 0; s < SPI; ++s) {
-                // (asm reads for the same reason as the tile reads: no wait on the DMA in flight)
+            for (int half = 0; half < kWaves; half += 8) {
                 f32x4 part[8];
 #pragma unroll
                 for (int w2 = 0; w2 < 8; ++w2)
-                    asm volatile("ds_read_b128 %0, %1" : "=v"(part[w2]) : "v"(lds_offset(red[bi & 1][w2][s][lane])));
+                    asm volatile("ds_read_b128 %0, %1" : "=v"(part[w2]) : "v"(lds_offset(red[q & 1][half + w2][lane])));
                 asm volatile("s_waitcnt lgkmcnt(0)"
                              : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]), "+v"(part[4]),
                                "+v"(part[5]), "+v"(part[6]), "+v"(part[7]));
-                f32x4 t = part[0];  // waves without a tile column wrote zeros
 #pragma unroll
-                for (int w2 = 1; w2 < 8; ++w2) t += part[w2];
-                const int64_t n = (strip0 + s) * kStripRows + r;
-                if (n < L.N) {
+                for (int w2 = 0; w2 < 8; ++w2) t += part[w2];
+            }
+            const int n = strip * kStripRows + r;
+            int ldy = a.ldy, ncols = L.N;
+            asm volatile("" : "+s"(ldy), "+s"(ncols));
+            if (n < L.N) {
+                const uint64_t Yp = reinterpret_cast<uint64_t>(a.Ypart) +
+                                    uint64_t(int64_t(chunk) * a.G + gi) * uint64_t(a.M) * uint64_t(L.N) * 4u;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int m = 4 * g4 + v;
-                        if (m >= a.M) continue;
-                        if (a.Ypart)
-                            ((g_float *)a.Ypart)[((int64_t(chunk) * a.G + gi) * a.M + m) * L.N + n] = t[v];
-                        else if (a.ydtype == MUW_F32)
-                            ((g_float *)Y)[int64_t(m) * a.ldy + n] = t[v];
-                        else
-                            ((g_u16 *)Y)[int64_t(m) * a.ldy + n] = f32_to_bf16_rne(t[v]);
-                    }
+                for (int v = 0; v < 4; ++v) {
+                    const int m = 4 * g4 + v;
+                    if (m >= a.M) continue;
+                    if (a.Ypart)
+                        *(g_float *)(Yp + uint64_t(uint32_t(m * ncols + n) * 4u)) = t[v];
+                    else if (a.ydtype == MUW_F32)
+                        *(g_float *)(Y + uint64_t(uint32_t(m * ldy + n) * 4u)) = t[v];
+                    else
+                        *(g_u16 *)(Y + uint64_t(uint32_t(m * ldy + n) * 2u)) = f32_to_bf16_rne(t[v]);
                 }
             }
         }
@@ -448,37 +479,27 @@ int device_cus()
 }
 
 template <int B, int NCH, int D>
-muw_status launch_stream_variant(StreamArgs a, const Layout &L, int64_t nstrips_total, hipStream_t st)
+muw_status launch_stream_variant(StreamArgs a, const Layout &L, hipStream_t st)
 {
     const StreamGeom geom{uint32_t(L.dir_off), uint32_t(L.streams_off), int32_t(L.KT), int32_t(L.NS),
                           int32_t(L.N), int32_t(L.K)};
     const int cus = device_cus();
-    // two strips per barrier when there is enough work to keep every compute unit busy anyway
-    const bool spi2 = (L.NS + 1) / 2 * int64_t(a.G) >= 2 * int64_t(cus);
-    const int SPI = spi2 ? 2 : 1;
-    a.nbpm = int((L.NS + SPI - 1) / SPI);
-    a.nbatches = a.nbpm * a.G;
-    int grid = a.nbatches < cus ? a.nbatches : cus;
-    a.per_wg = (a.nbatches + grid - 1) / grid;
-    grid = (a.nbatches + a.per_wg - 1) / a.per_wg;
+    a.nstrips = int32_t(L.NS) * a.G;
+    int grid = a.nstrips < cus ? a.nstrips : cus;
+    a.per_wg = (a.nstrips + grid - 1) / grid;
+    grid = (a.nstrips + a.per_wg - 1) / a.per_wg;
     dim3 g(unsigned(grid), unsigned(a.nchunk), 1);
-    (void)nstrips_total;
-    if (spi2)
-        k_stream_bf16<B, NCH, D, 2><<<g, 512, 0, st>>>(a, geom);
-    else
-        k_stream_bf16<B, NCH, D, 1><<<g, 512, 0, st>>>(a, geom);
+    k_stream_bf16<B, NCH, D><<<g, kWaves * 64, 0, st>>>(a, geom);
     return hip_status(hipGetLastError());
 }
 
 template <int B>
 muw_status launch_stream_b(StreamArgs a, const Layout &L, int nch, hipStream_t st)
 {
-    const int64_t total = L.NS * int64_t(a.G);
+    // per-wave ring of (D + 1) * NCH KiB; 16 rings + the reduction buffers fit the 160 KiB of LDS
     switch (nch) {
-    case 1:
-    case 2: return launch_stream_variant<B, 2, 6>(a, L, total, st);
-    case 3: return launch_stream_variant<B, 3, 4>(a, L, total, st);
-    case 4: return launch_stream_variant<B, 4, 3>(a, L, total, st);
+    case 1: return launch_stream_variant<B, 1, 6>(a, L, st);
+    case 2: return launch_stream_variant<B, 2, 3>(a, L, st);
     default: return MUW_EUNSUPPORTED;
     }
 }
@@ -490,8 +511,9 @@ muw_status launch_stream_b(StreamArgs a, const Layout &L, int nch, hipStream_t s
 bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 {
     if (d.wdtype != MUW_BF16 || a.M > 16 || a.M < 1) return false;
-    if (d.max_tile_bytes <= 0 || d.max_tile_bytes > 4096) return false;
+    if (d.max_tile_bytes <= 0 || d.max_tile_bytes > 2048) return false;
     if (L.K % 8 != 0 || a.ldx % 8 != 0) return false;
+    if (a.ldx >= (1 << 26) || a.ldy >= (1 << 26) || L.N >= (1 << 26)) return false;  // 32-bit offsets in the kernel
     if (!a.blobs && (reinterpret_cast<uintptr_t>(a.X) & 15u)) return false;
     if (a.G > 32767 || L.NS * int64_t(a.G) > (int64_t(1) << 30)) return false;
     return true;
@@ -499,7 +521,7 @@ bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &
 
 size_t stream_gemm_workspace_bytes(const Layout &L, int64_t M, int G)
 {
-    const int64_t nchunk = (L.KT + 7) / 8;
+    const int64_t nchunk = (L.KT + kWaves - 1) / kWaves;
     return nchunk > 1 ? size_t(nchunk) * size_t(G) * size_t(M) * size_t(L.N) * sizeof(float) : 0;
 }
 
@@ -514,10 +536,10 @@ muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs
     a.Ys = g.Ys;
     a.G = g.blobs ? g.G : 1;
     a.M = int32_t(g.M);
-    a.ldx = g.ldx;
-    a.ldy = g.ldy;
+    a.ldx = int32_t(g.ldx);
+    a.ldy = int32_t(g.ldy);
     a.ydtype = g.ydtype;
-    a.nchunk = int32_t((L.KT + 7) / 8);
+    a.nchunk = int32_t((L.KT + kWaves - 1) / kWaves);
     a.Ypart = a.nchunk > 1 ? static_cast<float *>(ws) : nullptr;
     const int nch = (d.max_tile_bytes + 1023) / 1024;
     muw_status rc;
