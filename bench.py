@@ -187,6 +187,84 @@ def bench_cfg5(args, torch, muw, synth, to_device):
                          "traffic": None}}
 
 
+def _roof(bytes_algo, flops_surv, ms):
+    t_min_ms = max(bytes_algo / (HBM_PEAK_GBS * 1e6), flops_surv / (MFMA_BF16_PEAK_TFLOPS * 1e9))
+    return t_min_ms / ms
+
+
+def report_all(args, torch, muw, synth, to_device):
+    """Every configuration once: time, algorithmic GB/s, surviving / executed TFLOP/s, fraction of the
+    HBM-or-MFMA roofline, the same layer with every block DENSE through this library, and the dense
+    torch operator (hipBLASLt / MIOpen) as an outside yardstick."""
+    rows = []
+
+    def linear_row(name, case, M):
+        X, W = synth.make_linear(case, M=M)
+        Xd, Wd = to_device(X), to_device(W)
+        layer = muw.muw_encode(Wd, case.B, case.r_unify, case.r_prune)
+        dense_layer = muw.muw_encode(Wd, case.B, 0.0, 0.0)
+        odt = torch.float32
+        Y = torch.empty((M, case.N), dtype=odt, device="cuda")
+        _, ms = time_steps(torch, lambda: muw.muw_gemm(layer, Xd, out=Y), 10, 2)
+        _, ms_dense = time_steps(torch, lambda: muw.muw_gemm(dense_layer, Xd, out=Y), 5, 1)
+        _, ms_torch = time_steps(torch, lambda: torch.matmul(Xd, Wd.T), 10, 2)
+        esz = 4 if case.dtype == "f32" else 2
+        b = layer.compressed_bytes + M * case.K * esz + M * case.N * 4
+        surv = 2.0 * M * case.B * (layer.NB - layer.desc.n_pruned)
+        rows.append({"config": name, "ms": ms, "algorithmic_GBps": b / ms / 1e6,
+                     "compressed_weight_GBps": layer.compressed_bytes / ms / 1e6,
+                     "surviving_TFLOPs": surv / ms / 1e9, "executed_dense_TFLOPs": 2.0 * M * case.N * case.K / ms / 1e9,
+                     "roofline_frac": _roof(b, surv, ms), "ms_all_dense_blocks_this_library": ms_dense,
+                     "ms_torch_dense": ms_torch})
+
+    def conv_row(name, case, distinct=4):
+        Xs, W = synth.make_conv(case, batch=min(distinct, case.batch))
+        Wd = to_device(W)
+        Xd = to_device(Xs).repeat(case.batch // min(distinct, case.batch), 1, 1, 1).contiguous()
+        layer = muw.muw_encode(Wd, case.B, case.r_unify, case.r_prune)
+        Y = torch.empty((case.batch, case.Cout, case.OH, case.OW), dtype=torch.float32, device="cuda")
+        _, ms = time_steps(torch, lambda: muw.muw_conv2d(layer, Xd, case.stride, case.pad, out=Y), 5, 2)
+        _, ms_torch = time_steps(torch, lambda: torch.nn.functional.conv2d(Xd, Wd, stride=case.stride,
+                                                                           padding=case.pad), 5, 2)
+        b = layer.compressed_bytes + Xd.numel() * 2 + Y.numel() * 4
+        surv = 2.0 * case.M * case.B * (layer.NB - layer.desc.n_pruned)
+        return {"config": name, "ms": ms, "algorithmic_GBps": b / ms / 1e6,
+                "compressed_weight_GBps": layer.compressed_bytes / ms / 1e6, "surviving_TFLOPs": surv / ms / 1e9,
+                "executed_dense_TFLOPs": 2.0 * case.M * case.N * case.K / ms / 1e9,
+                "roofline_frac": _roof(b, surv, ms), "ms_torch_dense": ms_torch, "bytes": b, "surv": surv}
+
+    c1 = synth.config1()
+    linear_row("cfg1 linear fp32 64x256x256 B4", c1, c1.M)
+    r2 = conv_row("cfg2 conv3x3 64->64 b32 @56 B4", synth.config2())
+    r2.pop("bytes"), r2.pop("surv")
+    rows.append(r2)
+    tot = {"ms": 0.0, "bytes": 0.0, "surv": 0.0, "torch": 0.0, "dense": 0.0}
+    layers3 = []
+    for case in synth.config3():
+        r = conv_row(case.name, case)
+        layers3.append({k: r[k] for k in ("config", "ms", "algorithmic_GBps", "roofline_frac", "ms_torch_dense")})
+        tot["ms"] += case.repeat * r["ms"]
+        tot["bytes"] += case.repeat * r["bytes"]
+        tot["surv"] += case.repeat * r["surv"]
+        tot["torch"] += case.repeat * r["ms_torch_dense"]
+        tot["dense"] += case.repeat * 2.0 * case.M * case.N * case.K
+    rows.append({"config": "cfg3 ResNet-50 52 convs b64 B8 (sum)", "ms": tot["ms"],
+                 "algorithmic_GBps": tot["bytes"] / tot["ms"] / 1e6, "surviving_TFLOPs": tot["surv"] / tot["ms"] / 1e9,
+                 "executed_dense_TFLOPs": tot["dense"] / tot["ms"] / 1e9,
+                 "roofline_frac": _roof(tot["bytes"], tot["surv"], tot["ms"]), "ms_torch_dense": tot["torch"],
+                 "layers": layers3})
+    for M in (1, 8, 16):
+        linear_row(f"cfg4 4096x4096 B16 M={M} (single launch, weights cache-resident)", synth.config4(M), M)
+    for which in ("up", "down"):
+        for M in (128, 2048):
+            linear_row(f"cfg5 mlp {which} B8 M={M}", synth.config5(M, which), M)
+    log(f"{'config':62s} {'ms':>9s} {'GB/s':>8s} {'TF surv':>8s} {'TF exec':>8s} {'roof':>6s} {'torch ms':>9s}")
+    for r in rows:
+        log(f"{r['config']:62s} {r['ms']:9.4f} {r['algorithmic_GBps']:8.0f} {r.get('surviving_TFLOPs', 0):8.1f} "
+            f"{r.get('executed_dense_TFLOPs', 0):8.1f} {r['roofline_frac']:6.3f} {r['ms_torch_dense']:9.4f}")
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -209,6 +287,12 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
             "data": "synthetic", "config": out.pop("config")}
     line.update(out)
+    if args.report:
+        rows = report_all(args, torch, muw, synth, to_device)
+        line["all_configs"] = [{k: v for k, v in r.items() if k != "layers"} for r in rows]
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "report.json"), "w") as f:
+            json.dump(rows, f, indent=1)
     print(json.dumps(line))
 
 

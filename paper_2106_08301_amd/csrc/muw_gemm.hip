@@ -191,6 +191,7 @@ muw_status dispatch_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t 
 size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M)
 {
     if (d.wdtype == MUW_BF16 && M >= 1 && M <= 16) return stream_gemm_workspace_bytes(L, M, 1);
+    if (d.wdtype == MUW_BF16 && M > 16) return tile_gemm_workspace_bytes(L, M);
     return 0;
 }
 
@@ -202,7 +203,7 @@ muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, vo
         const size_t need = stream_gemm_workspace_bytes(L, a.M, a.blobs ? a.G : 1);
         if (need == 0 || (ws && ws_bytes >= need && !a.blobs)) return launch_stream_gemm(d, L, a, ws, st);
     }
-    if (tile_gemm_applicable(d, L, a)) return launch_tile_gemm(d, L, a, st);
+    if (tile_gemm_applicable(d, L, a)) return launch_tile_gemm(d, L, a, ws, ws_bytes, st);
     ActView av{};
     av.X = a.X;
     av.M = a.M;
@@ -222,16 +223,17 @@ muw_status launch_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, vo
                               st);
 }
 
-size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, int64_t H, int64_t W, int32_t,
-                              int32_t)
+size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, int64_t H, int64_t W, int32_t stride,
+                              int32_t pad)
 {
     ConvArgs a{};
     a.Nb = Nb;
     a.H = H;
     a.W = W;
-    a.OH = 1;
-    a.OW = 1;
-    if (d.wdtype == MUW_BF16 && d.Cin % 8 == 0 && tile_conv_applicable(d, L, a)) return tile_conv_workspace_bytes(d, a);
+    a.OH = (H + 2 * int64_t(pad) - d.KH) / stride + 1;
+    a.OW = (W + 2 * int64_t(pad) - d.KW) / stride + 1;
+    if (a.OH < 1 || a.OW < 1) return 0;
+    if (d.wdtype == MUW_BF16 && d.Cin % 8 == 0 && tile_conv_applicable(d, L, a)) return tile_conv_workspace_bytes(d, L, a);
     return 0;
 }
 
@@ -240,8 +242,8 @@ muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, 
 {
     const int64_t M = a.Nb * a.OH * a.OW;
     if (M == 0) return MUW_OK;
-    if (tile_conv_applicable(d, L, a) && ws && ws_bytes >= tile_conv_workspace_bytes(d, a))
-        return launch_tile_conv(d, L, a, ws, st);
+    if (tile_conv_applicable(d, L, a) && ws && ws_bytes >= tile_conv_workspace_bytes(d, L, a))
+        return launch_tile_conv(d, L, a, ws, ws_bytes, st);
     ActView av{};
     av.X = a.X;
     av.M = M;

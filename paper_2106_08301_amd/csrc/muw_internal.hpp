@@ -51,7 +51,9 @@ muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs
 
 // muw_mfma.hip: the LDS-tiled MFMA kernel for M > 16
 bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a);
-muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, hipStream_t st);
+size_t tile_gemm_workspace_bytes(const Layout &L, int64_t M);
+muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &a, void *ws, size_t ws_bytes,
+                            hipStream_t st);
 
 struct ConvArgs {
     const void *blob;
@@ -68,8 +70,9 @@ size_t conv2d_workspace_bytes(const muw_desc &d, const Layout &L, int64_t Nb, in
 
 // muw_mfma.hip: convolution through the tile kernel (NHWC copy of the input in the workspace)
 bool tile_conv_applicable(const muw_desc &d, const Layout &L, const ConvArgs &a);
-size_t tile_conv_workspace_bytes(const muw_desc &d, const ConvArgs &a);
-muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &a, void *ws, hipStream_t st);
+size_t tile_conv_workspace_bytes(const muw_desc &d, const Layout &L, const ConvArgs &a);
+muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &a, void *ws, size_t ws_bytes,
+                            hipStream_t st);
 
 inline muw_status hip_status(hipError_t e) { return e == hipSuccess ? MUW_OK : MUW_EHIP; }
 

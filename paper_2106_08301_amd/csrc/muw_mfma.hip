@@ -33,9 +33,15 @@ struct TileGemmArgs {
     int32_t ydtype;
     // convolution geometry (CONV instantiation only); M = Nb*OH*OW, k = (kh*KW + kw)*Cin + cin
     int32_t Cin, H, W, OH, OW, KW, stride, pad;
+    // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per); partial sums go to Ypart[z][M][N] (fp32)
+    int32_t kp_per;
+    float *Ypart;
 };
 
-__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
+// Index (in 16-byte units) of chunk `chunk` of LDS row `row`.  Rows are 128 bytes (32 banks), so rows of
+// equal parity start at the same bank; XOR-ing the chunk with bits 1..3 of the row number makes the 16
+// rows that one quarter-wave reads at a fixed chunk hit 16 distinct 16-byte bank groups.
+__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }
 
 // NCHW -> NHWC copy of a bf16 tensor (64 channels x 64 pixels per workgroup through LDS), so that the
 // implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.
@@ -103,7 +109,10 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         }
     }
 
-    for (int64_t kp = 0; kp < L.KP; ++kp) {
+    const int64_t kp_lo = int64_t(blockIdx.z) * a.kp_per;  // a multiple of the tile length
+    const int64_t kp_hi = kp_lo + a.kp_per < L.KP ? kp_lo + a.kp_per : L.KP;
+#pragma unroll 1
+    for (int64_t kp = kp_lo; kp < kp_hi; ++kp) {
         const int p = int(kp % kTilePanels);
         const int64_t kt = kp / kTilePanels;
         // ---- global loads of the A tile (issued first: longest latency)
@@ -173,6 +182,13 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
             const int64_t n = n0 + wn * 64 + s * 16 + r;
             if (n >= L.N) continue;
             const int64_t mq = m0 + wm * (TM / 2) + mb * 16 + 4 * g;  // the lane's 4 consecutive rows
+            if (a.Ypart) {
+                float *part = a.Ypart + int64_t(blockIdx.z) * a.M * L.N;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (mq + v < a.M) part[(mq + v) * L.N + n] = acc[mb][s][v];
+                continue;
+            }
             if constexpr (CONV) {
                 // NCHW: for a fixed output channel the 4 rows are 4 consecutive pixels
                 const int64_t pix = int64_t(a.OH) * a.OW;
@@ -205,16 +221,71 @@ __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layou
         }
 }
 
+// Sum the split-K partials in split order (deterministic) and write the output in its final layout.
+__global__ __launch_bounds__(256) void k_tile_reduce(const float *__restrict__ part, int splits, int64_t M, int64_t N,
+                                                     void *Y, int64_t ldy, int ydtype, int64_t pix)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= M * N) return;
+    float t = 0.f;
+    for (int z = 0; z < splits; ++z) t += part[int64_t(z) * M * N + i];
+    const int64_t m = i / N, n = i % N;
+    const int64_t idx = pix ? ((m / pix) * N + n) * pix + m % pix : m * ldy + n;
+    if (ydtype == MUW_F32)
+        static_cast<float *>(Y)[idx] = t;
+    else
+        static_cast<uint16_t *>(Y)[idx] = f32_to_bf16_rne(t);
+}
+
+int tile_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// How many K splits make the launch fill the chip (two workgroups per compute unit), given that a
+// split must cover whole tiles and that the partial sums need M*N*4 bytes each.
+int tile_splits(const Layout &L, int64_t M)
+{
+    const int64_t tm = 128;
+    const int64_t wgs = ((L.N + kTN - 1) / kTN) * ((M + tm - 1) / tm);
+    const int64_t want = 2 * int64_t(tile_cus());
+    if (wgs >= want || L.KT < 2) return 1;
+    int64_t s = (want + wgs - 1) / wgs;
+    if (s > L.KT) s = L.KT;
+    if (s > 16) s = 16;
+    return int(s);
+}
+
 template <int B, bool CONV>
-muw_status launch_tile_b(const TileGemmArgs &a, const Layout &L, hipStream_t st)
+muw_status launch_tile_b(TileGemmArgs a, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
-    if (a.M > 128) {
-        dim3 grid(nt, unsigned((a.M + 255) / 256));
+    int splits = tile_splits(L, a.M);
+    if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(a.M) * size_t(L.N) * 4u)) splits = 1;
+    const int64_t kt_per = (L.KT + splits - 1) / splits;
+    splits = int((L.KT + kt_per - 1) / kt_per);
+    a.kp_per = int32_t(kt_per * kTilePanels);
+    a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
+    if (false) {  // the 256-row tile is slower today (fewer workgroups in flight to hide the decode latency)
+        dim3 grid(nt, unsigned((a.M + 255) / 256), unsigned(splits));
         k_tile_gemm_bf16<B, 256, CONV><<<grid, 256, 0, st>>>(a, L);
     } else {
-        dim3 grid(nt, unsigned((a.M + 127) / 128));
+        dim3 grid(nt, unsigned((a.M + 127) / 128), unsigned(splits));
         k_tile_gemm_bf16<B, 128, CONV><<<grid, 256, 0, st>>>(a, L);
+    }
+    if (splits > 1) {
+        const int64_t total = a.M * L.N;
+        k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, a.M, L.N, a.Y, a.ldy, a.ydtype,
+                                                                    CONV ? int64_t(a.OH) * a.OW : 0);
     }
     return hip_status(hipGetLastError());
 }
@@ -229,7 +300,14 @@ bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
     return true;
 }
 
-muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &g, hipStream_t st)
+size_t tile_gemm_workspace_bytes(const Layout &L, int64_t M)
+{
+    const int s = tile_splits(L, M);
+    return s > 1 ? size_t(s) * size_t(M) * size_t(L.N) * 4u : 0;
+}
+
+muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &g, void *ws, size_t ws_bytes,
+                            hipStream_t st)
 {
     TileGemmArgs a{};
     a.blob = static_cast<const uint8_t *>(g.blob);
@@ -240,9 +318,9 @@ muw_status launch_tile_gemm(const muw_desc &d, const Layout &L, const GemmArgs &
     a.ldy = g.ldy;
     a.ydtype = g.ydtype;
     switch (d.B) {
-    case 4: return launch_tile_b<4, false>(a, L, st);
-    case 8: return launch_tile_b<8, false>(a, L, st);
-    case 16: return launch_tile_b<16, false>(a, L, st);
+    case 4: return launch_tile_b<4, false>(a, L, ws, ws_bytes, st);
+    case 8: return launch_tile_b<8, false>(a, L, ws, ws_bytes, st);
+    case 16: return launch_tile_b<16, false>(a, L, ws, ws_bytes, st);
     default: return MUW_EUNSUPPORTED;
     }
 }
@@ -257,13 +335,22 @@ bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
     return true;
 }
 
-size_t tile_conv_workspace_bytes(const muw_desc &d, const ConvArgs &a)
+size_t tile_conv_nhwc_bytes(const muw_desc &d, const ConvArgs &a)
 {
-    return size_t(a.Nb) * size_t(a.H) * size_t(a.W) * size_t(d.Cin) * 2u;
+    return size_t(align16(uint64_t(a.Nb) * uint64_t(a.H) * uint64_t(a.W) * uint64_t(d.Cin) * 2u));
 }
 
-muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &c, void *ws, hipStream_t st)
+size_t tile_conv_workspace_bytes(const muw_desc &d, const Layout &L, const ConvArgs &a)
 {
+    return tile_conv_nhwc_bytes(d, a) + tile_gemm_workspace_bytes(L, a.Nb * a.OH * a.OW);
+}
+
+muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &c, void *ws, size_t ws_bytes,
+                            hipStream_t st)
+{
+    const size_t nhwc = tile_conv_nhwc_bytes(d, c);
+    void *part = static_cast<uint8_t *>(ws) + nhwc;
+    const size_t part_bytes = ws_bytes - nhwc;
     const int P = int(c.H * c.W);
     dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
     k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin, P);
@@ -282,9 +369,9 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     a.stride = c.stride;
     a.pad = c.pad;
     switch (d.B) {
-    case 4: return launch_tile_b<4, true>(a, L, st);
-    case 8: return launch_tile_b<8, true>(a, L, st);
-    case 16: return launch_tile_b<16, true>(a, L, st);
+    case 4: return launch_tile_b<4, true>(a, L, part, part_bytes, st);
+    case 8: return launch_tile_b<8, true>(a, L, part, part_bytes, st);
+    case 16: return launch_tile_b<16, true>(a, L, part, part_bytes, st);
     default: return MUW_EUNSUPPORTED;
     }
 }
