@@ -20,6 +20,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -37,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg5", "copy"])
     ap.add_argument("--groups", type=int, default=128, help="distinct encoded matrices per launch (cfg4)")
     ap.add_argument("--distinct", type=int, default=4, help="matrices generated from distinct seeds (cfg4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,7 +186,7 @@ def bench_cfg5(args, torch, muw, synth, to_device):
             "config": {"workload": "cfg5_mlp_M2048"}, "per_gemm": res,
             "roofline": {"bound": "mfma", "achieved": total_flops_surv / total_ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": total_flops_surv / total_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                         "traffic": None}}
+                         "traffic": traffic_from_profiles("k_tile_gemm_bf16_cfg5")}}
 
 
 def _roof(bytes_algo, flops_surv, ms):
@@ -273,11 +275,26 @@ def main():
 
     from paper_2106_08301_amd import binding as muw
     from paper_2106_08301_amd import synth
-    from tests.gpu_util import to_device
+
+    def to_device(t):
+        a = np.ascontiguousarray(t.data)
+        if t.dtype == "f32":
+            return torch.from_numpy(a).cuda()
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    if args.workload == "copy":
+        # Calibration for the rocprofv3 HBM counters: a plain device copy of known size (256 MiB read,
+        # 256 MiB written per step).  Not a benchmark of this library.
+        n = 256 << 20
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        _, ms = time_steps(torch, lambda: dst.copy_(src), args.steps, args.warmup)
+        print(json.dumps({"workload": "copy_calibration", "bytes_read": n, "bytes_written": n, "ms_per_step": ms,
+                          "GBps_read_plus_write": 2 * n / ms / 1e6}))
+        return
     if args.workload == "cfg4":
         out = bench_cfg4(args, torch, muw, synth, to_device)
     else:
