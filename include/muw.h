@@ -53,16 +53,19 @@ typedef enum {
 } muw_layout;
 
 /* Plain-old-data description of one encoded layer; caller-owned, lives on the HOST.
- * The caller fills N, K, B, KH, KW, Cin, wdtype; muw_encode fills n_unified, n_pruned and
- * max_tile_bytes. */
+ * The caller fills N, K, B, KH, KW, Cin, wdtype; muw_encode fills n_unified, n_pruned,
+ * max_tile_bytes and max_quad_bytes. */
 typedef struct {
     int64_t N, K;         /* GEMM view of the layer: Y[M][N] = X[M][K] * W[N][K]^T */
     int32_t B;            /* block length along K; K % B == 0 (convolution: Cin % B == 0) */
     int32_t KH, KW, Cin;  /* 1, 1, K for a linear layer; K == KH*KW*Cin */
     int32_t wdtype;       /* muw_dtype of the weights, of the stored magnitudes and dense blocks */
-    int32_t max_tile_bytes; /* largest tile stream of the blob (written by muw_encode; 0 = unknown:
-                             the fast small-M kernel is then not used).  For muw_gemm_grouped it
-                             must be >= the value of every layer in the group. */
+    int32_t max_tile_bytes; /* largest tile stream of the blob (written by muw_encode) */
+    int32_t max_quad_bytes; /* largest run of 4 tile streams of one strip that starts at a tile column
+                             divisible by 4 (written by muw_encode; 0 = unknown: the fast small-M
+                             kernel is then not used).  For muw_gemm_grouped both must be >= the
+                             values of every layer in the group. */
+    int32_t reserved;       /* keep 0 */
     int64_t n_unified;    /* number of UNIFIED blocks (written by muw_encode) */
     int64_t n_pruned;     /* number of PRUNED blocks  (written by muw_encode) */
 } muw_desc;

@@ -24,7 +24,7 @@ EXPORTED = ["muw_version", "muw_status_str", "muw_counts", "muw_encode_sizes", "
 
 class muw_desc(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("B", C.c_int32), ("KH", C.c_int32),
-                ("KW", C.c_int32), ("Cin", C.c_int32), ("wdtype", C.c_int32), ("max_tile_bytes", C.c_int32),
+                ("KW", C.c_int32), ("Cin", C.c_int32), ("wdtype", C.c_int32), ("max_tile_bytes", C.c_int32), ("max_quad_bytes", C.c_int32), ("reserved", C.c_int32),
                 ("n_unified", C.c_int64), ("n_pruned", C.c_int64)]
 
 
@@ -106,7 +106,7 @@ def muw_counts(NB, r_unify, r_prune):
 
 
 def make_desc(N, K, B, wdtype, KH=1, KW=1, Cin=None):
-    return muw_desc(N=N, K=K, B=B, KH=KH, KW=KW, Cin=K if Cin is None else Cin, wdtype=wdtype, max_tile_bytes=0,
+    return muw_desc(N=N, K=K, B=B, KH=KH, KW=KW, Cin=K if Cin is None else Cin, wdtype=wdtype, max_tile_bytes=0, max_quad_bytes=0, reserved=0,
                     n_unified=0, n_pruned=0)
 
 
@@ -194,6 +194,7 @@ class GemmGroup:
     def __init__(self, layers, Xs, out_dtype=torch.float32):
         d = muw_desc.from_buffer_copy(layers[0].desc)
         d.max_tile_bytes = max(l.desc.max_tile_bytes for l in layers)
+        d.max_quad_bytes = max(l.desc.max_quad_bytes for l in layers)
         self.desc, self.layers, self.Xs = d, layers, Xs
         self.M = Xs[0].shape[0]
         dev = Xs[0].device

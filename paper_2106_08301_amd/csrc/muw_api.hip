@@ -34,7 +34,7 @@ size_t blob_upper_bound(const Layout &L, int64_t n_u, int64_t n_d)
     b += uint64_t(n_d) * uint64_t(L.B) * uint64_t(L.vb);             // dense payload
     b += uint64_t(n_u) * uint64_t(L.vb);                             // magnitudes
     b += (uint64_t(n_u) * uint64_t(L.B) + 7) / 8;                    // sign bits
-    b += uint64_t(L.NT) * 17u;                                       // per-tile rounding and padding
+    b += uint64_t(L.NT) * 33u;                                       // per-tile rounding and padding
     return size_t(align16(b));
 }
 
@@ -104,14 +104,15 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
     int64_t n_u, n_p;
     muw_counts(L.N * L.KB, r_unify, r_prune, &n_u, &n_p);
     bool nonfinite = false;
-    int32_t max_tile = 0;
+    int32_t max_tile[2] = {0, 0};
     rc = launch_encode(*desc, L, W_dev, int(layout), n_u, n_p, blob_dev, need_blob, ws_dev,
-                       static_cast<hipStream_t>(hip_stream), &nonfinite, &max_tile);
+                       static_cast<hipStream_t>(hip_stream), &nonfinite, max_tile);
     if (rc != MUW_OK) return rc;
     if (nonfinite) return MUW_ENONFINITE;
     desc->n_unified = n_u;
     desc->n_pruned = n_p;
-    desc->max_tile_bytes = max_tile;
+    desc->max_tile_bytes = max_tile[0];
+    desc->max_quad_bytes = max_tile[1];
     return MUW_OK;
 }
 

@@ -25,6 +25,7 @@ struct SelState {
     uint32_t hist[256];
     uint32_t nonfinite;
     uint32_t max_tile_bytes;
+    uint32_t max_quad_bytes;
 };
 
 struct TileCount {
@@ -257,24 +258,32 @@ __global__ __launch_bounds__(256) void k_directory(const TileCount *counts, Layo
                                                    int64_t n_u, int64_t n_p, SelState *state)
 {
     __shared__ uint64_t part[256];
-    __shared__ uint32_t biggest;
-    if (threadIdx.x == 0) biggest = 0;
+    __shared__ uint32_t biggest, biggest_quad;
+    if (threadIdx.x == 0) biggest = biggest_quad = 0;
     __syncthreads();
     DirEntry *dir = reinterpret_cast<DirEntry *>(blob + L.dir_off);
     const int64_t per = (L.NT + 255) / 256;
     const int64_t lo = int64_t(threadIdx.x) * per, hi = (lo + per < L.NT) ? lo + per : L.NT;
     uint64_t sum = 0;
-    uint32_t mx = 0;
+    uint32_t mx = 0, mxq = 0;
     for (int64_t t = lo; t < hi; ++t) {
         const uint32_t b = tile_bytes(L, panels_in_tile(L, t % L.KT), counts[t].nU, counts[t].nD);
         sum += b;
         mx = b > mx ? b : mx;
+        if ((t % L.KT) % 4 == 0) {  // a quad = 4 tile columns of one strip, starting at a multiple of 4
+            uint32_t quad = b;
+            for (int64_t u = t + 1; u < t + 4 && u % L.KT != 0 && u < L.NT; ++u)
+                quad += tile_bytes(L, panels_in_tile(L, u % L.KT), counts[u].nU, counts[u].nD);
+            mxq = quad > mxq ? quad : mxq;
+        }
     }
     part[threadIdx.x] = sum;
     atomicMax(&biggest, mx);
+    atomicMax(&biggest_quad, mxq);
     __syncthreads();
     if (threadIdx.x == 0) {
         state->max_tile_bytes = biggest;
+        state->max_quad_bytes = biggest_quad;
         uint64_t run = 0;
         for (int i = 0; i < 256; ++i) {
             uint64_t t = part[i];
@@ -391,7 +400,7 @@ __global__ __launch_bounds__(256) void k_pack(const T *W, int layout, int Cin, i
                     store_mag(&mag, block_q<T, B>(raw));
                     uint32_t qbits = 0;
                     if constexpr (sizeof(T) == 2) qbits = mag.bits;
-                    reinterpret_cast<uint32_t *>(mags)[rku] = qbits | (field << 16);
+                    reinterpret_cast<uint32_t *>(mags)[rku] = pack_record16(qbits, field);
                     continue;
                 }
                 store_mag(&mags[rku], block_q<T, B>(raw));
@@ -553,12 +562,13 @@ muw_status encode_typed(const muw_desc &d, const Layout &L, const void *W, int l
                                              L, blob);
     if (hipGetLastError() != hipSuccess) return MUW_EHIP;
 
-    uint32_t result[2] = {0, 0};  // nonfinite, max_tile_bytes (adjacent in SelState)
+    uint32_t result[3] = {0, 0, 0};  // nonfinite, max_tile_bytes, max_quad_bytes (adjacent in SelState)
     if (hipMemcpyAsync(result, &state->nonfinite, sizeof(result), hipMemcpyDeviceToHost, st) != hipSuccess)
         return MUW_EHIP;
     if (hipStreamSynchronize(st) != hipSuccess) return MUW_EHIP;
     *nonfinite = result[0] != 0;
-    *max_tile_bytes = int32_t(result[1]);
+    max_tile_bytes[0] = int32_t(result[1]);
+    max_tile_bytes[1] = int32_t(result[2]);
     return MUW_OK;
 }
 

@@ -23,7 +23,7 @@ EncodeWorkspace encode_workspace(const Layout &L);
 
 muw_status launch_encode(const muw_desc &d, const Layout &L, const void *W, int layout, int64_t n_u,
                          int64_t n_p, void *blob, size_t blob_bytes, void *ws, hipStream_t st,
-                         bool *nonfinite, int32_t *max_tile_bytes);
+                         bool *nonfinite, int32_t *max_tile_bytes /* [2]: largest tile, largest quad of tiles */);
 muw_status launch_export(const muw_desc &d, const Layout &L, const void *blob, uint8_t *tags,
                          uint16_t *signs, void *mags, hipStream_t st);
 muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, void *What,

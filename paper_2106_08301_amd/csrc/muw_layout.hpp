@@ -14,12 +14,16 @@
 //           block j is UNIFIED / DENSE.  Neither bit: PRUNED (or outside the matrix).  2 bits per block.
 //           The mask area always spans 4 panels (a ragged last tile has zero masks for the panels it
 //           lacks), so payload offsets do not depend on the tile's position.
-//   dense   the B values of each DENSE block, in (panel, sub-step, lane) order
-//   mags    one stored magnitude per UNIFIED block, same order
+//   mags    one stored magnitude per UNIFIED block, in (panel, sub-step, lane) order
 //   signs   B bits per UNIFIED block, same order, bit-packed; inside a block the bits are permuted
 //           (sign_pos) so that the bf16 decode is one shift and one bit-select per output dword
-//           (B = 16 with bf16 storage: mags and signs are interleaved instead, one 32-bit record
-//           {magnitude, sign field} per UNIFIED block, so a block costs a single 4-byte read)
+//           (B = 16 with bf16 storage: mags and signs are interleaved instead, one 32-bit record per
+//           UNIFIED block, bytes {magnitude low, sign field low, magnitude high, sign field high}: a
+//           block costs a single 4-byte read and the record itself is the sign word of the decode --
+//           bits 15 - d and 31 - d hold the signs of elements 2 d and 2 d + 1, see pack_record16)
+//   dense   the B values of each DENSE block, same order, starting at the next multiple of 16 bytes
+//   Masks first and dense last: every offset inside a tile, and the tile's size, follow from the
+//   popcounts of its masks alone (the streaming kernel never needs the directory to decode).
 // Because payload order is (panel, sub-step, lane), the payload index of a lane's block is the
 // running count of earlier blocks plus the popcount of the mask below the lane (v_mbcnt): PRUNED
 // blocks cost 2 mask bits and nothing else (Sec. 3.1: storage of pruned blocks is skipped).
@@ -85,10 +89,11 @@ __host__ __device__ inline int panels_in_tile(const Layout &L, int64_t kt)
 __host__ __device__ inline uint32_t tile_bytes(const Layout &L, int npanels, uint32_t nU, uint32_t nD)
 {
     (void)npanels;
-    uint32_t b = uint32_t(kTilePanels) * 2u * uint32_t(L.S) * 8u;
+    uint32_t b = uint32_t(kTilePanels) * 2u * uint32_t(L.S) * 8u;  // masks
+    b += nU * uint32_t(L.vb);                                      // magnitudes
+    b += (nU * uint32_t(L.B) + 7u) / 8u;                           // sign bits
+    b = uint32_t(align16(b));                                      // dense blocks start 16-byte aligned
     b += nD * uint32_t(L.B) * uint32_t(L.vb);
-    b += nU * uint32_t(L.vb);
-    b += (nU * uint32_t(L.B) + 7u) / 8u;
     return uint32_t(align16(b));
 }
 
@@ -119,14 +124,26 @@ __device__ inline TileStreams tile_streams(int B, int vb, int npanels, uint32_t 
 {
     TileStreams t;
     (void)npanels;
-    t.dense_off = uint32_t(kTilePanels) * 2u * uint32_t(16 / B) * 8u;
-    t.mag_off = t.dense_off + nD * uint32_t(B) * uint32_t(vb);
+    (void)nD;
+    t.mag_off = uint32_t(kTilePanels) * 2u * uint32_t(16 / B) * 8u;
     t.sign_off = t.mag_off + nU * uint32_t(vb);
+    t.dense_off = (t.sign_off + (nU * uint32_t(B) + 7u) / 8u + 15u) & ~15u;
     return t;
 }
 
 // bf16 storage with B = 16 keeps {magnitude, sign field} of a UNIFIED block in one 32-bit record.
 __host__ __device__ constexpr bool interleaved_records(int B, int vb) { return B == 16 && vb == 2; }
+
+// The 32-bit record of a B = 16 bf16 UNIFIED block (q: 15 magnitude bits, field: sign_pos-permuted signs).
+__host__ __device__ inline uint32_t pack_record16(uint32_t q, uint32_t field)
+{
+    return (q & 0xffu) | ((field & 0xffu) << 8) | ((q & 0xff00u) << 8) | ((field & 0xff00u) << 16);
+}
+__host__ __device__ inline void unpack_record16(uint32_t rec, uint32_t &q, uint32_t &field)
+{
+    q = (rec & 0xffu) | ((rec >> 8) & 0xff00u);
+    field = ((rec >> 8) & 0xffu) | ((rec >> 16) & 0xff00u);
+}
 
 // Magnitude bits and B-bit sign field of the UNIFIED block with payload index `rank`.
 // VB = value bytes (2: bf16 bits in the low half of q, 4: fp32 bits).
@@ -136,8 +153,7 @@ __device__ inline void load_unified(const uint8_t *tile, const TileStreams &ts, 
 {
     if constexpr (interleaved_records(B, VB)) {
         const uint32_t rec = reinterpret_cast<const uint32_t *>(tile + ts.mag_off)[rank];
-        q = rec & 0xffffu;
-        s = rec >> 16;
+        unpack_record16(rec, q, s);
     } else {
         if constexpr (VB == 2)
             q = reinterpret_cast<const uint16_t *>(tile + ts.mag_off)[rank];

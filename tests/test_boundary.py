@@ -48,7 +48,8 @@ def test_sizes_and_compressed_bytes(muw):
     algo = muw.lib.muw_compressed_bytes(C.byref(d))
     # 2 bits per block + (16 + 16) bits per unified block + 16*16 bits per dense block
     assert algo == (2 * 1048576 + 734003 * 32 + 52429 * 256) // 8
-    assert algo <= blob <= algo * 1.03             # directory (8 B per 256-k tile), padding to 16 B
+    # the buffer bound: directory (8 B per 256-k tile) and at most two 16-byte paddings per tile
+    assert algo <= blob <= algo * 1.04
     assert ws > 0
 
 
