@@ -2,24 +2,21 @@
 // time is the time to stream the compressed weights from HBM once (paper Sec. 3.2: the stored form of
 // a pruned block is nothing, of a unified block one magnitude and B sign bits).
 //
-// The kernel is bound by vector-instruction issue (about one instruction per bf16 pair of decoded
-// weights is the floor), so everything that is not decode runs on the scalar unit or not at all:
-//   - persistent workgroups of 4 wavefronts, two per compute unit.  Wave w owns the quad of tile
-//     columns 4 w .. 4 w + 3 (1024 consecutive k) and keeps the activations of those columns (all
-//     M <= 16 rows: 128 registers of MFMA A-operands) for as long as the workgroup stays on one matrix;
-//   - the quad's byte stream (4 tile streams, adjacent in the blob) goes HBM -> LDS with
-//     global_load_lds_dwordx4 (no registers, no VALU) D strips ahead, into a per-wave ring of D + 1 slots;
-//   - directory entries and the tile masks are fetched with scalar loads straight into scalar
-//     registers (the masks one tile ahead; the lines are in L2 by then because the DMA asked for them
-//     first), so masks cost no vector instruction; a lane finds its payload by v_mbcnt, reads it from
-//     LDS (pruned blocks read nothing) and turns the record into bf16 pairs with one shift and one
-//     bit-select per dword, straight into the B-operand of two 16x16x32 bf16 MFMAs per panel;
-//   - the 4 partial 16x16 accumulators of a strip are summed through LDS by one wave (the role
-//     rotates) and written to Y.  No atomics: results are bitwise reproducible.
-// Every quad issues exactly NCHS 1-KiB DMA instructions (lanes past the end of the stream re-read its
-// last 16 bytes) and every iteration one more for a directory span, so "strip q has landed" is a static
-// vmcnt wait.  Inside a quad everything follows from the tile masks (record and dense offsets, the
-// tile's size, hence the next tile's address): the directory is needed only for the quad's span.
+// One persistent workgroup of 16 wavefronts per compute unit (4 per SIMD: the kernel is bound by
+// instruction issue, so it needs the thread-level parallelism).  Wave w keeps the activations of tile
+// column kt = 16 c + w (256 consecutive k, all M <= 16 rows: 32 VGPRs of MFMA A-operands) in registers
+// for as long as the workgroup stays on one weight matrix, and walks down the strips (16 output rows)
+// of that tile column:
+//   - the tile's byte stream goes HBM -> LDS with global_load_lds_dwordx4 (no registers, no VALU),
+//     D tiles ahead of the one being decoded, into a per-wave ring of D + 1 slots;
+//   - masks are read from the LDS copy one tile ahead and made scalar (v_readfirstlane); the lane
+//     finds its payload by v_mbcnt, reads it from LDS (pruned blocks read nothing) and turns
+//     its 32-bit record into bf16 pairs with one shift and one bit-select per dword, straight into
+//     the B-operand of two 16x16x32 bf16 MFMAs per panel;
+//   - the 16 partial 16x16 accumulators of a strip (one per tile column) are summed through LDS by one
+//     wave (the role rotates) and written to Y.  No atomics: results are bitwise reproducible.
+// Every tile issues exactly NCH 1-KiB DMA instructions (lanes past the end of the stream re-read its
+// last 16 bytes), so "tiles q and q + 1 have landed" is the static wait vmcnt((D - 1) * NCH).
 #include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
@@ -40,12 +37,9 @@ typedef __attribute__((address_space(1))) float g_float;
 typedef __attribute__((address_space(1))) uint16_t g_u16;
 typedef const __attribute__((address_space(4))) uint64_t c_u64;
 
-constexpr int kWaves = 4;                   // wavefronts per workgroup
-constexpr int kCols = 4;                    // tile columns per wavefront (a "quad": contiguous in the blob)
-constexpr int kChunkCols = kWaves * kCols;  // tile columns per workgroup (4096 k); more K goes to blockIdx.y
-constexpr int kP = kTilePanels;             // panels per tile (4)
+constexpr int kWaves = 16;       // wavefronts per workgroup = tile columns handled at once
+constexpr int kP = kTilePanels;  // panels per tile (4)
 static_assert(kP == 4, "the streaming kernel is written for 4-panel tiles");
-typedef const __attribute__((address_space(4))) uint32_t c_u32;
 
 struct StreamArgs {
     const uint8_t *blob;
@@ -137,66 +131,66 @@ __device__ inline uint64_t uniform64(uint64_t v)
 }
 
 // ------------------------------------------------------------------------------------------------
-// B = 16: the tile's 8 masks (4 panels x {U, D}) are the first 64 bytes of its stream.
+// B = 16: the tile's 8 masks (4 panels x {U, D}) are 64 bytes, read from LDS one tile ahead.
 // ------------------------------------------------------------------------------------------------
 struct TileMasks16 {
     uint64_t u[kP], d[kP];
 };
+struct RawMasks16 {
+    u32x4_t v[kP];  // {U lo, U hi, D lo, D hi} of one panel, identical in every lane
+};
 
-// Scalar load of a tile's masks from the blob (address is wave-uniform).
-__device__ inline void load_masks16(TileMasks16 &m, uint64_t tile_addr)
+__device__ inline void lds_read_masks16(RawMasks16 &mv, uint32_t addr)
 {
-    c_u64 *p = (c_u64 *)tile_addr;
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\t"
+                 "ds_read_b128 %2, %4 offset:32\n\tds_read_b128 %3, %4 offset:48"
+                 : "=&v"(mv.v[0]), "=&v"(mv.v[1]), "=&v"(mv.v[2]), "=&v"(mv.v[3])
+                 : "v"(addr));
+}
+
+__device__ inline void scalar_masks16(const RawMasks16 &mv, TileMasks16 &m)
+{
 #pragma unroll
     for (int i = 0; i < kP; ++i) {
-        m.u[i] = p[2 * i];
-        m.d[i] = p[2 * i + 1];
+        // (the builtin returns a signed int: go through uint32_t before widening)
+        const uint32_t ulo = __builtin_amdgcn_readfirstlane(mv.v[i].x), uhi = __builtin_amdgcn_readfirstlane(mv.v[i].y);
+        const uint32_t dlo = __builtin_amdgcn_readfirstlane(mv.v[i].z), dhi = __builtin_amdgcn_readfirstlane(mv.v[i].w);
+        m.u[i] = (uint64_t(uhi) << 32) | ulo;
+        m.d[i] = (uint64_t(dhi) << 32) | dlo;
     }
 }
 
-// Bytes of a B = 16 bf16 tile stream, from its masks: 64 (masks) + 4 per UNIFIED block, rounded up to
-// 16, + 32 per DENSE block.  `dense_rel` = offset of the first DENSE block.
-__device__ inline uint32_t tile_bytes16(const TileMasks16 &m, uint32_t &dense_rel)
+// One tile (4 panels) of a B = 16 layer: issue every payload read (and the raw masks of the next
+// tile), wait once, then decode and feed 8 MFMAs.
+__device__ inline void process_tile16(uint32_t tile_lds, const TileMasks16 &m, uint32_t nU, const uint4 (&xr)[kP][2],
+                                      f32x4 &acc0, f32x4 &acc1, uint32_t next_tile_lds, RawMasks16 &mv)
 {
-    uint32_t nU = 0, nD = 0;
-#pragma unroll
-    for (int p = 0; p < kP; ++p) {
-        nU += uint32_t(__popcll(m.u[p]));
-        nD += uint32_t(__popcll(m.d[p]));
-    }
-    dense_rel = kP * 16u + ((nU * 4u + 15u) & ~15u);
-    return dense_rel + nD * 32u;
-}
-
-// One tile (4 panels) of a B = 16 layer: issue every payload read, wait once, run `mid` (scalar and
-// DMA work that should overlap the decode), decode, 8 MFMAs.
-// Record layout (pack_record16): bytes {q low, signs of even elements, q high, signs of odd elements},
-// so (rec << d) has the signs of elements 2 d and 2 d + 1 at bits 15 and 31.
-template <int T, typename Mid>
-__device__ inline void process_tile16(uint32_t tile_lds, uint32_t dense_rel, const TileMasks16 &m,
-                                      const uint4 (&xr)[kCols * kP][2], f32x4 &acc0, f32x4 &acc1, uint64_t &extra,
-                                      Mid mid)
-{
-    uint32_t s_rec = tile_lds + kP * 16u;      // scalar: running LDS address of the next record
-    uint32_t s_dense = tile_lds + dense_rel;   // scalar: running LDS address of the next DENSE block
+    // stream order: masks | records | DENSE blocks (from the next multiple of 16 bytes)
+    const uint32_t rec_off = kP * 16u;
+    const uint32_t dense_off = rec_off + ((nU * 4u + 15u) & ~15u);
     uint32_t rec[kP];
     u32x4_t wlo[kP], whi[kP];
+    uint32_t ru = 0, rd = 0;
+    lds_read_masks16(mv, next_tile_lds);
 #pragma unroll
     for (int p = 0; p < kP; ++p) {
-        // Every lane reads (a lane without a UNIFIED block reads a neighbour's record and drops it
+        // Every lane reads (a lane without a UNIFIED block reads its neighbour's record and drops it
         // below): an unconditional read leaves no register copy between the read and the wait.
-        rec[p] = lds_read_b32(s_rec + 4u * mbcnt64(m.u[p]));
-        if (__builtin_amdgcn_inverse_ballot_w64(m.d[p])) lds_read_2xb128(wlo[p], whi[p], s_dense + 32u * mbcnt64(m.d[p]));
-        s_rec += 4u * uint32_t(__popcll(m.u[p]));
-        s_dense += 32u * uint32_t(__popcll(m.d[p]));
+        rec[p] = lds_read_b32(tile_lds + rec_off + 4u * (ru + mbcnt64(m.u[p])));
+        if (__builtin_amdgcn_inverse_ballot_w64(m.d[p]))
+            lds_read_2xb128(wlo[p], whi[p], tile_lds + dense_off + 32u * (rd + mbcnt64(m.d[p])));
+        ru += __popcll(m.u[p]);
+        rd += __popcll(m.d[p]);
     }
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(rec[0]), "+v"(rec[1]), "+v"(rec[2]), "+v"(rec[3]), "+v"(wlo[0]), "+v"(wlo[1]),
-                   "+v"(wlo[2]), "+v"(wlo[3]), "+v"(whi[0]), "+v"(whi[1]), "+v"(whi[2]), "+v"(whi[3]), "+v"(extra));
-    mid();
+                   "+v"(wlo[2]), "+v"(wlo[3]), "+v"(whi[0]), "+v"(whi[1]), "+v"(whi[2]), "+v"(whi[3]),
+                   "+v"(mv.v[0]), "+v"(mv.v[1]), "+v"(mv.v[2]), "+v"(mv.v[3]));
 #pragma unroll
     for (int p = 0; p < kP; ++p) {
         if (!__builtin_amdgcn_inverse_ballot_w64(m.d[p])) {
+            // record (pack_record16): bytes {q low, signs of even elements, q high, signs of odd
+            // elements}: (rec << d) has the signs of elements 2 d and 2 d + 1 at bits 15 and 31
             const uint32_t rc = __builtin_amdgcn_inverse_ballot_w64(m.u[p]) ? rec[p] : 0u;
             const uint32_t qq = __builtin_amdgcn_perm(rc, rc, 0x02000200u);
             wlo[p].x = qq | (rc & 0x80008000u);
@@ -208,41 +202,26 @@ __device__ inline void process_tile16(uint32_t tile_lds, uint32_t dense_rel, con
             whi[p].z = qq | ((rc << 6) & 0x80008000u);
             whi[p].w = qq | ((rc << 7) & 0x80008000u);
         }
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[T * kP + p][0]),
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][0]),
                                                        __builtin_bit_cast(bf16x8, wlo[p]), acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[T * kP + p][1]),
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][1]),
                                                        __builtin_bit_cast(bf16x8, whi[p]), acc1, 0, 0, 0);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// B = 4, 8: same walk, panel by panel, masks read from the LDS copy when needed (not tuned: these
-// block lengths are not on the memory-bound benchmark).
+// B = 4, 8: same walk, panel by panel, masks read from LDS when needed (not tuned: these block
+// lengths are not on the memory-bound benchmark).
 // ------------------------------------------------------------------------------------------------
-// Block counts of a tile from its masks in the blob (scalar loads).
 template <int B>
-__device__ inline void tile_counts_small_b(uint64_t tile_addr, uint32_t &nU, uint32_t &nD)
-{
-    constexpr int S = 16 / B;
-    c_u64 *p = (c_u64 *)tile_addr;
-    nU = nD = 0;
-#pragma unroll 1
-    for (int pn = 0; pn < kP; ++pn)
-#pragma unroll
-        for (int jj = 0; jj < S; ++jj) {
-            nU += uint32_t(__popcll(p[pn * 2 * S + jj]));
-            nD += uint32_t(__popcll(p[pn * 2 * S + S + jj]));
-        }
-}
-
-template <int B, int T>
-__device__ inline uint32_t process_tile_small_b(uint32_t tile_lds, uint32_t nU, uint32_t nD,
-                                                const uint4 (&xr)[kCols * kP][2], f32x4 &acc0, f32x4 &acc1)
+__device__ inline void process_tile_small_b(uint32_t tile_lds, uint32_t nU, uint32_t nD, const uint4 (&xr)[kP][2],
+                                            f32x4 &acc0, f32x4 &acc1)
 {
     constexpr int S = 16 / B;
     constexpr uint32_t mag_off = kP * 2u * S * 8u;
     const uint32_t sign_off = mag_off + nU * 2u;
     const uint32_t dense_off = (sign_off + (nU * uint32_t(B) + 7u) / 8u + 15u) & ~15u;
+    (void)nD;
     uint32_t ru = 0, rd = 0;
 #pragma unroll
     for (int p = 0; p < kP; ++p) {
@@ -286,303 +265,187 @@ __device__ inline uint32_t process_tile_small_b(uint32_t tile_lds, uint32_t nU, 
             }
         }
         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, xr[T * kP + p][0]), __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3])),
+            __builtin_bit_cast(bf16x8, xr[p][0]), __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3])),
             acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-            __builtin_bit_cast(bf16x8, xr[T * kP + p][1]), __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7])),
+            __builtin_bit_cast(bf16x8, xr[p][1]), __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7])),
             acc1, 0, 0, 0);
     }
-    return (dense_off + nD * uint32_t(B) * 2u + 15u) & ~15u;  // bytes of this tile stream
 }
 
-// Where a workgroup is in its sequence of strips (which runs over all matrices of a grouped call).
-struct Cursor {
-    int32_t gi, strip;
-    uint64_t blob;
-};
-
-struct StreamKernArgs {
-    StreamArgs a;
-    StreamGeom L;
-};
-// A kernel argument read where it is used (through the scalar cache) instead of being kept in a
-// scalar register for the whole kernel: the loop needs those registers for the tile masks.
-template <typename T>
-__device__ inline T kernarg(size_t offset)
+template <int B, int NCH, int D>
+__global__ __launch_bounds__(kWaves * 64) void k_stream_bf16(StreamArgs a, StreamGeom L)
 {
-    const __attribute__((address_space(4))) uint8_t *p =
-        (const __attribute__((address_space(4))) uint8_t *)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(p));  // opaque: keeps the load from being hoisted out of the loop
-    return *(const __attribute__((address_space(4))) T *)(p + offset);
-}
-#define MUW_KARG(type, field) kernarg<type>(offsetof(StreamKernArgs, field))
-
-// SLOT512: bytes of a ring slot in units of 512 (>= the largest quad of the blob).
-template <int B, int SLOT512, int D>
-__global__ __launch_bounds__(kWaves * 64, 2) void k_stream_bf16(StreamKernArgs)
-{
-    constexpr int SLOT = SLOT512 * 512;
-    constexpr int NCHS = (SLOT + 1023) / 1024;  // DMA instructions per quad
+    constexpr int SLOT = NCH * 1024;
     constexpr int NSLOT = D + 1;
-    constexpr int NSPAN = 2 * D + 1;
-    constexpr int PER_ITER = NCHS + 1;  // DMA instructions per steady-state iteration (span + quad)
     __shared__ __attribute__((aligned(16))) uint8_t ring[kWaves][NSLOT * SLOT];
     __shared__ __attribute__((aligned(16))) float red[2][kWaves][64][4];
-    // {first, one-past-last} stream offset of the wave's quad in upcoming strips (fetched by DMA far
-    // ahead: a scalar load of a cold directory line would stall every wait on the scalar/LDS counter)
-    __shared__ __attribute__((aligned(8))) uint32_t spans[kWaves][NSPAN][2];
 
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
-    const int lane = threadIdx.x & 63;
-    const int kt0 = int(blockIdx.y) * kChunkCols + wave * kCols;
-    // the few arguments the loop needs all the time
-    const uint32_t KT = MUW_KARG(int32_t, L.KT), NS = MUW_KARG(int32_t, L.NS);
-    const uint32_t dir_off = MUW_KARG(uint32_t, L.dir_off), streams_off = MUW_KARG(uint32_t, L.streams_off);
-    const int ncols = int(KT) - kt0 < kCols ? int(KT) - kt0 : kCols;  // tile columns this wave has (<= 0: none)
-    const bool active = ncols > 0;
+    const int lane = threadIdx.x & 63, r = lane & 15, g4 = lane >> 4;
+    const int chunk = blockIdx.y;
+    const int kt = chunk * kWaves + wave;
+    const bool active = kt < L.KT;
 
-    int nseq;   // this workgroup's strips, over all matrices: element q = strip s_lo + q
-    Cursor cc;  // strip being decoded
-    {
-        const int per_wg = MUW_KARG(int32_t, a.per_wg), nstrips = MUW_KARG(int32_t, a.nstrips);
-        const int s_lo = blockIdx.x * per_wg;
-        int s_hi = s_lo + per_wg;
-        if (s_hi > nstrips) s_hi = nstrips;
-        if (s_lo >= s_hi) return;
-        nseq = s_hi - s_lo;
-        cc.gi = s_lo / int(NS);
-        cc.strip = s_lo % int(NS);
-    }
-    const uint32_t myring = lds_offset(ring[wave]);
+    const int s_lo = blockIdx.x * a.per_wg;
+    int s_hi = s_lo + a.per_wg;
+    if (s_hi > a.nstrips) s_hi = a.nstrips;
+    if (s_lo >= s_hi) return;
+    const int nseq = s_hi - s_lo;  // this workgroup's strips, over all matrices: element q = strip s_lo + q
+    uint8_t *myring = ring[wave];
 
-    auto blob_of = [&](int gi) -> uint64_t {
-        const void *const *blobs = MUW_KARG(const void *const *, a.blobs);
-        return blobs ? table_entry(blobs, gi) : reinterpret_cast<uint64_t>(MUW_KARG(const uint8_t *, a.blob));
-    };
-    auto advance = [&](Cursor &c) {  // (callers never step past the last strip of the last matrix)
-        if (++c.strip == int(NS)) {
-            c.strip = 0;
-            ++c.gi;
-            c.blob = blob_of(c.gi);
+    // ---- directory window: lane l holds stream address, size and counts of sequence element qbase + l
+    int qbase = 0;
+    uint64_t q_addr = 0;
+    uint32_t q_bytes = 0, q_cnt = 0;
+    auto refill = [&](int base) {
+        qbase = base;
+        const int qq = base + lane;
+        const int gs = s_lo + qq;
+        const int gi = gs / L.NS;
+        const int64_t strip = gs % L.NS;
+        const bool ok = active && qq < nseq;
+        uint64_t blob = reinterpret_cast<uint64_t>(a.blob);
+        if (a.blobs) blob = ((const __attribute__((address_space(1))) uint64_t *)a.blobs)[ok ? gi : 0];
+        q_addr = blob;  // a valid 16 bytes for elements with nothing to fetch
+        q_bytes = 16;
+        q_cnt = 0;
+        if (ok) {
+            g_cu32 *de = (g_cu32 *)(blob + L.dir_off + uint64_t(strip * L.KT + kt) * sizeof(DirEntry));
+            const uint32_t off16 = de[0], cnt = de[1], next = de[2];
+            q_addr = blob + L.streams_off + uint64_t(off16) * 16;
+            q_bytes = (next - off16) * 16;
+            q_cnt = cnt;  // nU | nD << 16
         }
+        // Drain on every path: a load left pending here would turn each later read of the window
+        // registers into a wait for all DMA prefetches as well.
+        wait_vmcnt<0>();
     };
-    // ---- DMA of the span {first, one-past-last offset} of the wave's quad in strip c: lanes 0 and 1
-    //      fetch one directory word each
-    auto issue_span = [&](const Cursor &c, int sslot) {
-        const uint64_t e = c.blob + dir_off + uint64_t(uint32_t(c.strip) * KT + uint32_t(kt0)) * sizeof(DirEntry);
-        if (lane < 2)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(e + (lane ? uint32_t(ncols) * 8u : 0u)),
-                                             (lds_void_t *)spans[wave][sslot], 4, 0, 0);
-    };
-    // ---- the NCHS DMA instructions of one quad into ring slot `slot`
-    auto issue_quad = [&](int slot, uint64_t base, uint32_t bytes) {
-        const uint32_t last = bytes - 16u;
+    // ---- issue the NCH DMA instructions of sequence element qi into its ring slot
+    auto issue = [&](int qi) {
+        const uint32_t alo = __builtin_amdgcn_readlane(uint32_t(q_addr), qi - qbase);
+        const uint32_t ahi = __builtin_amdgcn_readlane(uint32_t(q_addr >> 32), qi - qbase);
+        const uint64_t base = (uint64_t(ahi) << 32) | alo;
+        const uint32_t last = __builtin_amdgcn_readlane(q_bytes, qi - qbase) - 16;
+        const int slot = qi % NSLOT;
 #pragma unroll
-        for (int c = 0; c < NCHS; ++c) {
+        for (int c = 0; c < NCH; ++c) {
             uint32_t off = uint32_t(c) * 1024u + uint32_t(lane) * 16u;
             off = off < last ? off : last;
-            if (c * 1024 + 1024 <= SLOT || lane < 32)  // (a slot may end in the middle of the last KiB)
-                __builtin_amdgcn_global_load_lds((global_void_t *)(base + off),
-                                                 (lds_void_t *)(ring[wave] + slot * SLOT + c * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_void_t *)(base + off),
+                                             (lds_void_t *)(myring + slot * SLOT + c * 1024), 16, 0, 0);
         }
     };
-    auto next_slot = [](int sl, int n) { return sl + 1 == n ? 0 : sl + 1; };
 
-    uint4 xr[kCols * kP][2];
+    uint4 xr[kP][2];
 #pragma unroll
-    for (int p = 0; p < kCols * kP; ++p) xr[p][0] = xr[p][1] = make_uint4(0, 0, 0, 0);
+    for (int p = 0; p < kP; ++p) xr[p][0] = xr[p][1] = make_uint4(0, 0, 0, 0);
     int cur_g = -1;
-
-    cc.blob = blob_of(cc.gi);
-    Cursor cq = cc;            // strip whose quad DMA is issued next (q + D in the loop)
-    Cursor cs = cc;            // strip whose span DMA is issued next (q + 2 D in the loop)
-    int n_cs = 0;              // its index in the sequence (stops at nseq - 1: then the last span is re-fetched)
-    uint64_t tg = 0;           // address in the blob of the tile decoded next
-    uint64_t fifo[D] = {};     // addresses of the quads of strips q + 1 .. q + D
-    TileMasks16 mk{};          // B = 16: masks of the tile decoded next
-    int slot_issue = 0, slot_proc = 0, span_issue = 0, span_read = 0;
-
-    auto step_span_cursor = [&]() {
-        if (n_cs + 1 < nseq) {
-            ++n_cs;
-            advance(cs);
-        }
-    };
-    // the quad of the strip at cursor cq: read its span (landed), issue its DMA, return its address
-    auto start_quad = [&](uint64_t span) -> uint64_t {
-        const uint32_t begin = __builtin_amdgcn_readfirstlane(uint32_t(span));
-        const uint32_t end = __builtin_amdgcn_readfirstlane(uint32_t(span >> 32));
-        const uint64_t base = cq.blob + streams_off + uint64_t(begin) * 16u;
-        issue_quad(slot_issue, base, (end - begin) * 16u);
-        slot_issue = next_slot(slot_issue, NSLOT);
-        return base;
-    };
+    uint64_t Ycur = 0;  // output matrix of the current weight matrix (kept in scalar registers)
+    RawMasks16 mv{};  // B = 16: raw masks of the tile that is decoded next
 
     if (active) {
-        // spans of strips 0 .. D - 1, then (as iterations -D .. -1 of the loop would) span j + 2 D and quad j + D
-        for (int i = 0; i < D; ++i) {
-            issue_span(cs, span_issue);
-            span_issue = next_slot(span_issue, NSPAN);
-            step_span_cursor();
+        refill(0);
+        for (int qi = 0; qi < D && qi < nseq; ++qi) issue(qi);
+        if constexpr (B == 16) {
+            wait_vmcnt<0>();  // once per workgroup: tile 0 must have landed before its masks are read
+            lds_read_masks16(mv, lds_offset(myring));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(mv.v[0]), "+v"(mv.v[1]), "+v"(mv.v[2]), "+v"(mv.v[3]));
         }
-        wait_vmcnt<0>();
-        for (int i = 0; i < D; ++i) {
-            issue_span(cs, span_issue);
-            span_issue = next_slot(span_issue, NSPAN);
-            step_span_cursor();
-            uint64_t span = lds_read_b64(lds_offset(spans[wave][span_read]));
-            span_read = next_slot(span_read, NSPAN);
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(span));
-            if (i < nseq) {
-                const uint64_t base = start_quad(span);
-                if (i == 0)
-                    tg = base;
-                else
-                    fifo[i - 1] = base;
-                if (i + 1 < nseq) advance(cq);
-            }
-        }
-        if constexpr (B == 16) load_masks16(mk, tg);
     }
 
+    int gi = s_lo / L.NS, strip = s_lo % L.NS - 1;  // matrix and strip of element q, stepped without dividing
     for (int q = 0; q < nseq; ++q) {
-        if (cc.gi != cur_g) {
-            cur_g = cc.gi;
-            if (active) {
-                const void *const *Xs = MUW_KARG(const void *const *, a.Xs);
-                const uint64_t X = Xs ? table_entry(Xs, cc.gi) : reinterpret_cast<uint64_t>(MUW_KARG(const uint16_t *, a.X));
-                const int ldx = MUW_KARG(int32_t, a.ldx), M = MUW_KARG(int32_t, a.M), K = MUW_KARG(int32_t, L.K);
-                const int r = lane & 15, g4 = lane >> 4;
+        if (++strip == L.NS) {
+            strip = 0;
+            ++gi;
+        }
+        const bool new_matrix = gi != cur_g;
+        if (new_matrix) {
+            cur_g = gi;
+            Ycur = a.Ys ? table_entry(a.Ys, gi) : reinterpret_cast<uint64_t>(a.Y);
+        }
+        if (new_matrix && active) {
+            const uint64_t X = a.Xs ? table_entry(a.Xs, gi) : reinterpret_cast<uint64_t>(a.X);
+            // (opaque copies: keep the address arithmetic of this rare path out of the loop-invariant
+            // registers the compiler would otherwise spill to scratch)
+            int ldx = a.ldx;
+            asm volatile("" : "+s"(ldx));
 #pragma unroll
-                for (int p = 0; p < kCols * kP; ++p)
+            for (int p = 0; p < kP; ++p)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int k = kt0 * kTileK + p * kPanelK + 16 * g4 + 8 * h;
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (r < M && k + 8 <= K) {
-                            const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
-                            v = make_uint4(t.x, t.y, t.z, t.w);
-                        }
-                        xr[p][h] = v;
+                for (int h = 0; h < 2; ++h) {
+                    const int k = kt * kTileK + p * kPanelK + 16 * g4 + 8 * h;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (r < a.M && k + 8 <= L.K) {
+                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
+                        v = make_uint4(t.x, t.y, t.z, t.w);
                     }
-                // Drain here, once per matrix, so that no later use of xr needs a wait that would also
-                // wait for the DMA prefetches in flight.
-                wait_vmcnt<0>();
-            }
+                    xr[p][h] = v;
+                }
+            // Drain here, once per matrix, so that no later use of xr needs a wait that would also
+            // wait for the DMA prefetches in flight.
+            wait_vmcnt<0>();
         }
         f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-        Cursor cn = cc;  // strip q + 1 (every wave steps: the reducing wave needs it even without tile columns)
-        if (q + 1 < nseq) advance(cn);
         if (active) {
-            // Quad q has landed, and so has the span of strip q + D: everything but the DMA of the last
-            // D - 1 iterations (which all issued a span and a quad if strip q + D - 1 exists).
-            if (q + D <= nseq)
-                wait_vmcnt<(D - 1) * PER_ITER>();
-            else
+            const int qi = q + D;
+            if (qi < nseq && qi >= qbase + 64) refill(q);  // keeps q .. q + 63: covers q, q + 1, q + D
+            const uint32_t cnt = __builtin_amdgcn_readlane(q_cnt, q - qbase);
+            // After this wait tiles q and q + 1 have landed (q + 1 because its masks are fetched while
+            // q is being decoded).
+            if (qi < nseq) {
+                issue(qi);
+                wait_vmcnt<(D - 1) * NCH>();
+            } else {
                 wait_vmcnt<0>();
-            uint64_t span = lds_read_b64(lds_offset(spans[wave][span_read]));  // waited for inside tile 0
-            span_read = next_slot(span_read, NSPAN);
-            // after the payload wait of tile 0: DMA for strip q + D (its span is in registers now) and
-            // the span of strip q + 2 D
-            auto start_dma = [&]() {
-                issue_span(cs, span_issue);
-                span_issue = next_slot(span_issue, NSPAN);
-                step_span_cursor();
-                if (q + D < nseq) {
-                    fifo[D - 1] = start_quad(span);
-                    if (q + D + 1 < nseq) advance(cq);
-                }
-            };
-            uint32_t tl = myring + uint32_t(slot_proc) * SLOT;
-            slot_proc = next_slot(slot_proc, NSLOT);
-            uint64_t unused = 0;
-#pragma unroll
-            for (int t = 0; t < kCols; ++t) {
-                if (t < ncols) {
-                    // the tile decoded after this one: next in the quad, else first of the next strip's
-                    // quad (after the very last tile: this one again, unused)
-                    const bool last_tile = t + 1 >= ncols;
-                    if constexpr (B == 16) {
-                        uint32_t dense_rel;
-                        const uint32_t tbytes = tile_bytes16(mk, dense_rel);
-                        uint64_t tg_next = tg + tbytes;
-                        if (last_tile) tg_next = q + 1 < nseq ? fifo[0] : tg;
-                        TileMasks16 mnext;
-                        auto mid = [&]() {
-                            if (t == 0) start_dma();
-                            // (opaque: the scalar load must not move above the wait it follows, or that
-                            // wait would include its latency)
-                            uint64_t addr = last_tile && t == 0 && q + 1 < nseq ? fifo[0] : tg_next;
-                            asm volatile("" : "+s"(addr));
-                            load_masks16(mnext, addr);
-                        };
-                        if (t == 0) process_tile16<0>(tl, dense_rel, mk, xr, acc0, acc1, span, mid);
-                        if (t == 1) process_tile16<1>(tl, dense_rel, mk, xr, acc0, acc1, unused, mid);
-                        if (t == 2) process_tile16<2>(tl, dense_rel, mk, xr, acc0, acc1, unused, mid);
-                        if (t == 3) process_tile16<3>(tl, dense_rel, mk, xr, acc0, acc1, unused, mid);
-                        mk = mnext;
-                        tg = tg_next;
-                        tl += tbytes;
-                    } else {
-                        if (t == 0) {
-                            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(span));
-                            start_dma();
-                        }
-                        uint32_t nU, nD, tbytes = 0;
-                        tile_counts_small_b<B>(tg, nU, nD);
-                        if (t == 0) tbytes = process_tile_small_b<B, 0>(tl, nU, nD, xr, acc0, acc1);
-                        if (t == 1) tbytes = process_tile_small_b<B, 1>(tl, nU, nD, xr, acc0, acc1);
-                        if (t == 2) tbytes = process_tile_small_b<B, 2>(tl, nU, nD, xr, acc0, acc1);
-                        if (t == 3) tbytes = process_tile_small_b<B, 3>(tl, nU, nD, xr, acc0, acc1);
-                        tg += tbytes;
-                        if (last_tile && q + 1 < nseq) tg = fifo[0];
-                        tl += tbytes;
-                    }
-                }
             }
-#pragma unroll
-            for (int i = 0; i + 1 < D; ++i) fifo[i] = fifo[i + 1];
+            const uint32_t tl = lds_offset(myring + (q % NSLOT) * SLOT);
+            if constexpr (B == 16) {
+                TileMasks16 sm;
+                scalar_masks16(mv, sm);
+                process_tile16(tl, sm, cnt & 0xffffu, xr, acc0, acc1, lds_offset(myring + ((q + 1) % NSLOT) * SLOT), mv);
+            } else {
+                process_tile_small_b<B>(tl, cnt & 0xffffu, cnt >> 16, xr, acc0, acc1);
+            }
         }
         *reinterpret_cast<f32x4 *>(red[q & 1][wave][lane]) = acc0 + acc1;
         lds_barrier();
         if (wave == (q & (kWaves - 1))) {
+            const uint64_t Y = Ycur;
             // (asm reads for the same reason as the tile reads: no wait on the DMA in flight)
-            f32x4 part[kWaves];
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};  // waves without a tile column wrote zeros
 #pragma unroll
-            for (int w2 = 0; w2 < kWaves; ++w2)
-                asm volatile("ds_read_b128 %0, %1" : "=v"(part[w2]) : "v"(lds_offset(red[q & 1][w2][lane])));
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]));
-            const f32x4 t = (part[0] + part[1]) + (part[2] + part[3]);  // waves without a tile column wrote zeros
-            const int r = lane & 15, g4 = lane >> 4;
-            const int n = cc.strip * kStripRows + r;
-            const int N = MUW_KARG(int32_t, L.N), M = MUW_KARG(int32_t, a.M);
-            float *Ypart = MUW_KARG(float *, a.Ypart);
-            if (n < N) {
-                if (Ypart) {
-                    const int G = MUW_KARG(int32_t, a.G);
-                    const uint64_t Yp = reinterpret_cast<uint64_t>(Ypart) +
-                                        uint64_t(int64_t(blockIdx.y) * G + cc.gi) * uint64_t(M) * uint64_t(N) * 4u;
+            for (int half = 0; half < kWaves; half += 8) {
+                f32x4 part[8];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (4 * g4 + v < M) *(g_float *)(Yp + uint64_t(uint32_t((4 * g4 + v) * N + n) * 4u)) = t[v];
-                } else {
-                    void *const *Ys = MUW_KARG(void *const *, a.Ys);
-                    const uint64_t Y = Ys ? table_entry(Ys, cc.gi) : reinterpret_cast<uint64_t>(MUW_KARG(void *, a.Y));
-                    const int ldy = MUW_KARG(int32_t, a.ldy);
-                    const bool f32out = MUW_KARG(int32_t, a.ydtype) == MUW_F32;
+                for (int w2 = 0; w2 < 8; ++w2)
+                    asm volatile("ds_read_b128 %0, %1" : "=v"(part[w2]) : "v"(lds_offset(red[q & 1][half + w2][lane])));
+                asm volatile("s_waitcnt lgkmcnt(0)"
+                             : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]), "+v"(part[4]),
+                               "+v"(part[5]), "+v"(part[6]), "+v"(part[7]));
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int m = 4 * g4 + v;
-                        if (m >= M) continue;
-                        if (f32out)
-                            *(g_float *)(Y + uint64_t(uint32_t(m * ldy + n) * 4u)) = t[v];
-                        else
-                            *(g_u16 *)(Y + uint64_t(uint32_t(m * ldy + n) * 2u)) = f32_to_bf16_rne(t[v]);
-                    }
+                for (int w2 = 0; w2 < 8; ++w2) t += part[w2];
+            }
+            const int n = strip * kStripRows + r;
+            int ldy = a.ldy, ncols = L.N;
+            asm volatile("" : "+s"(ldy), "+s"(ncols));
+            if (n < L.N) {
+                const uint64_t Yp = reinterpret_cast<uint64_t>(a.Ypart) +
+                                    uint64_t(int64_t(chunk) * a.G + gi) * uint64_t(a.M) * uint64_t(L.N) * 4u;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = 4 * g4 + v;
+                    if (m >= a.M) continue;
+                    if (a.Ypart)
+                        *(g_float *)(Yp + uint64_t(uint32_t(m * ncols + n) * 4u)) = t[v];
+                    else if (a.ydtype == MUW_F32)
+                        *(g_float *)(Y + uint64_t(uint32_t(m * ldy + n) * 4u)) = t[v];
+                    else
+                        *(g_u16 *)(Y + uint64_t(uint32_t(m * ldy + n) * 2u)) = f32_to_bf16_rne(t[v]);
                 }
             }
         }
-        cc = cn;
     }
 }
 
@@ -618,33 +481,30 @@ int device_cus()
     return cus;
 }
 
-template <int B, int SLOT512, int D>
+template <int B, int NCH, int D>
 muw_status launch_stream_variant(StreamArgs a, const Layout &L, hipStream_t st)
 {
     const StreamGeom geom{uint32_t(L.dir_off), uint32_t(L.streams_off), int32_t(L.KT), int32_t(L.NS),
                           int32_t(L.N), int32_t(L.K)};
-    const int wgs = 2 * device_cus();  // two workgroups per compute unit
+    const int cus = device_cus();
     a.nstrips = int32_t(L.NS) * a.G;
-    int grid = a.nstrips < wgs ? a.nstrips : wgs;
+    int grid = a.nstrips < cus ? a.nstrips : cus;
     a.per_wg = (a.nstrips + grid - 1) / grid;
     grid = (a.nstrips + a.per_wg - 1) / a.per_wg;
     dim3 g(unsigned(grid), unsigned(a.nchunk), 1);
-    k_stream_bf16<B, SLOT512, D><<<g, kWaves * 64, 0, st>>>(StreamKernArgs{a, geom});
+    k_stream_bf16<B, NCH, D><<<g, kWaves * 64, 0, st>>>(a, geom);
     return hip_status(hipGetLastError());
 }
 
 template <int B>
-muw_status launch_stream_b(StreamArgs a, const Layout &L, int quad_bytes, hipStream_t st)
+muw_status launch_stream_b(StreamArgs a, const Layout &L, int nch, hipStream_t st)
 {
-    // Per-wave ring of (D + 1) slots that hold one quad each; two workgroups (4 rings + reduction
-    // buffers each) share the 160 KiB of LDS of a compute unit while a slot is at most 5.5 KiB.
-    const int slot512 = (quad_bytes + 511) / 512;
-    if (slot512 <= 8) return launch_stream_variant<B, 8, 2>(a, L, st);
-    if (slot512 <= 10) return launch_stream_variant<B, 10, 2>(a, L, st);
-    if (slot512 <= 11) return launch_stream_variant<B, 11, 2>(a, L, st);
-    if (slot512 <= 12) return launch_stream_variant<B, 12, 2>(a, L, st);
-    if (slot512 <= 16) return launch_stream_variant<B, 16, 2>(a, L, st);
-    return MUW_EUNSUPPORTED;
+    // per-wave ring of (D + 1) * NCH KiB; 16 rings + the reduction buffers fit the 160 KiB of LDS
+    switch (nch) {
+    case 1: return launch_stream_variant<B, 1, 6>(a, L, st);
+    case 2: return launch_stream_variant<B, 2, 3>(a, L, st);
+    default: return MUW_EUNSUPPORTED;
+    }
 }
 
 }  // namespace
@@ -654,17 +514,17 @@ muw_status launch_stream_b(StreamArgs a, const Layout &L, int quad_bytes, hipStr
 bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 {
     if (d.wdtype != MUW_BF16 || a.M > 16 || a.M < 1) return false;
-    if (d.max_quad_bytes <= 0 || d.max_quad_bytes > 8192) return false;
+    if (d.max_tile_bytes <= 0 || d.max_tile_bytes > 2048) return false;
     if (L.K % 8 != 0 || a.ldx % 8 != 0) return false;
     if (a.ldx >= (1 << 26) || a.ldy >= (1 << 26) || L.N >= (1 << 26)) return false;  // 32-bit offsets in the kernel
     if (!a.blobs && (reinterpret_cast<uintptr_t>(a.X) & 15u)) return false;
-    if (a.G > 32767 || L.NS * int64_t(a.G) > (int64_t(1) << 30) || L.NT >= (int64_t(1) << 28)) return false;
+    if (a.G > 32767 || L.NS * int64_t(a.G) > (int64_t(1) << 30)) return false;
     return true;
 }
 
 size_t stream_gemm_workspace_bytes(const Layout &L, int64_t M, int G)
 {
-    const int64_t nchunk = (L.KT + kChunkCols - 1) / kChunkCols;
+    const int64_t nchunk = (L.KT + kWaves - 1) / kWaves;
     return nchunk > 1 ? size_t(nchunk) * size_t(G) * size_t(M) * size_t(L.N) * sizeof(float) : 0;
 }
 
@@ -682,13 +542,14 @@ muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs
     a.ldx = int32_t(g.ldx);
     a.ldy = int32_t(g.ldy);
     a.ydtype = g.ydtype;
-    a.nchunk = int32_t((L.KT + kChunkCols - 1) / kChunkCols);
+    a.nchunk = int32_t((L.KT + kWaves - 1) / kWaves);
     a.Ypart = a.nchunk > 1 ? static_cast<float *>(ws) : nullptr;
+    const int nch = (d.max_tile_bytes + 1023) / 1024;
     muw_status rc;
     switch (d.B) {
-    case 4: rc = launch_stream_b<4>(a, L, d.max_quad_bytes, st); break;
-    case 8: rc = launch_stream_b<8>(a, L, d.max_quad_bytes, st); break;
-    case 16: rc = launch_stream_b<16>(a, L, d.max_quad_bytes, st); break;
+    case 4: rc = launch_stream_b<4>(a, L, nch, st); break;
+    case 8: rc = launch_stream_b<8>(a, L, nch, st); break;
+    case 16: rc = launch_stream_b<16>(a, L, nch, st); break;
     default: return MUW_EUNSUPPORTED;
     }
     if (rc != MUW_OK) return rc;
