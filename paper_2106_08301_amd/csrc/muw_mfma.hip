@@ -11,8 +11,12 @@
 //           weights as two swizzled 16-byte chunks of row n
 //   MFMA    waves in a 2 x 2 grid, wave tile (TM/2) x 64: per step 2 x (TM/32) x 4 v_mfma_f32_16x16x32_bf16
 // The k order inside a panel is the decode order (lane group g owns k = 16 g .. 16 g + 15; MFMA h takes
-// 8 h .. 8 h + 7 of them), applied identically to both operands.  fp32 accumulation, no split-K: the
-// result is bitwise reproducible.  Two workgroups per compute unit hide each other's load/decode phase.
+// 8 h .. 8 h + 7 of them), applied identically to both operands.  fp32 accumulation; a launch that would
+// not fill the chip splits K into fp32 partial sums added in split order, so results are bitwise
+// reproducible.  Two workgroups per compute unit hide each other's load/decode phase.  Linear layers with
+// B = 8, 16 and K a multiple of 64 take the software-pipelined kernel of muw_mfma_pipe.hpp instead.
+#include <type_traits>
+
 #include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
@@ -253,9 +257,8 @@ int tile_cus()
 
 // How many K splits make the launch fill the chip (two workgroups per compute unit), given that a
 // split must cover whole tiles and that the partial sums need M*N*4 bytes each.
-int tile_splits(const Layout &L, int64_t M)
+int tile_splits(const Layout &L, int64_t M, int64_t tm = 128)
 {
-    const int64_t tm = 128;
     const int64_t wgs = ((L.N + kTN - 1) / kTN) * ((M + tm - 1) / tm);
     const int64_t want = 2 * int64_t(tile_cus());
     if (wgs >= want || L.KT < 2) return 1;
@@ -265,9 +268,14 @@ int tile_splits(const Layout &L, int64_t M)
     return int(s);
 }
 
+#include "muw_mfma_pipe.hpp"
+
 template <int B, bool CONV>
 muw_status launch_tile_b(TileGemmArgs a, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
+    if constexpr (!CONV) {
+        if (pipe_applicable<B>(a, L)) return launch_pipe<B>(a, L, ws, ws_bytes, st);
+    }
     const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
     int splits = tile_splits(L, a.M);
     if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(a.M) * size_t(L.N) * 4u)) splits = 1;
@@ -375,5 +383,15 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     default: return MUW_EUNSUPPORTED;
     }
 }
+
+#ifdef MUW_PROFILE_TILE
+extern "C" int muw_debug_tile_prof(unsigned long long *out8, int reset)
+{
+    unsigned long long z[8] = {};
+    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tile_prof), sizeof(z)) != hipSuccess) return 1;
+    if (reset && hipMemcpyToSymbol(HIP_SYMBOL(g_tile_prof), z, sizeof(z)) != hipSuccess) return 1;
+    return 0;
+}
+#endif
 
 }  // namespace muw

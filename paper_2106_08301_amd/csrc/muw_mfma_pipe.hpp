@@ -1,0 +1,518 @@
+// muw_mfma_pipe.hpp -- included by muw_mfma.hip (inside its unnamed namespace, after the helpers it uses).
+//
+// Linear layers with K a multiple of 64 and B = 8 or 16: the LDS-tiled MFMA GEMM of muw_mfma.hip, software
+// pipelined (paper Sec. 3.2: the layer is a blocked GEMM whose weight tile is decoded on the fly).
+//   - the activation tile is triple buffered in LDS and filled by global_load_lds two steps ahead;
+//   - the compressed payload of a step is gathered into registers two steps ahead (payload index by
+//     v_mbcnt over masks in scalar registers).  Every wait on the scalar/LDS counter also waits for the
+//     scalar loads in flight, so those must hit a cache: the mask lines of a tile stream are touched by a
+//     small DMA one tile before its first scalar load, directory entries are loaded two tiles ahead;
+//   - the payload of step t + 1 is decoded into the other weight buffer while the MFMAs of step t run;
+//   - one barrier per 64-k step.
+#pragma once
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+typedef __attribute__((address_space(1))) const u32x4_t g_cu32x4;
+typedef __attribute__((address_space(1))) const uint32_t g_cu32;
+typedef __attribute__((address_space(1))) const uint16_t g_cu16;
+typedef __attribute__((address_space(1))) const uint8_t g_cu8;
+typedef const __attribute__((address_space(4))) uint64_t c_u64;
+typedef const __attribute__((address_space(4))) uint32_t c_u32;
+
+template <int N>
+__device__ inline void wait_vmcnt_imm()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    // gfx9 s_waitcnt: vmcnt = simm16[15:14]:[3:0], expcnt = [6:4], lgkmcnt = [11:8] (left untouched)
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+// LDS reads of DMA-filled memory are inline assembly: for an ordinary LDS load that may alias a pending
+// global_load_lds the compiler waits for ALL pending vector-memory operations first, which would
+// serialise the prefetches behind this step's operand reads.  LDS operations complete in order, so a
+// counted wait lgkmcnt(n) issued after n younger reads guarantees the older ones (other outstanding
+// LDS or scalar operations only make it stricter).
+template <int OFF>
+__device__ inline u32x4_t lds_read_b128_at(uint32_t addr)
+{
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+// acc += a * b with the accumulator pinned in the accumulation registers: left to the compiler, the 128
+// accumulators of a 256-row tile take the ordinary registers and everything else is shuffled through
+// the accumulation registers by copies (which also forces early waits on loaded values).  Dependent
+// accumulations are at least four MFMAs apart in this file, so no wait states are missing.
+__device__ inline void mfma_acc(f32x4 &acc, const u32x4_t &a, const u32x4_t &b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Scalar state of one strip of the decode duty: where its current tile stream is and how many blocks
+// of it the panels before the next one hold.
+struct StripCursor {
+    uint64_t tile;                  // address of the tile stream
+    uint32_t sign_off;              // B = 8: offset of the sign bytes
+    uint32_t dense_off;             // offset of the DENSE blocks
+    uint32_t ru, rd;                // UNIFIED / DENSE blocks before the next panel
+    uint32_t nU;                    // UNIFIED blocks of the tile
+    bool live;                      // false: a strip past the last row of W (decodes to zeros)
+    uint32_t next_off16, next_cnt;  // directory entry of the strip's next tile (loaded two tiles ahead)
+    uint32_t next2_off16, next2_cnt;  // and of the one after
+};
+
+// Masks of one strip-panel (scalar registers).
+template <int B>
+struct PanelMasks {
+    uint64_t u[16 / B], d[16 / B];
+};
+template <int B>
+__device__ inline void load_panel_masks(uint64_t tile, int p, PanelMasks<B> &m)
+{
+    constexpr int S = 16 / B;
+    c_u64 *src = (c_u64 *)(tile + uint32_t(p) * (2u * S * 8u));
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        m.u[j] = src[j];
+        m.d[j] = src[S + j];
+    }
+}
+
+template <int B>
+struct Payload;  // what one lane loads for one strip-panel
+template <>
+struct Payload<16> {
+    uint32_t rec;
+    u32x4_t w0, w1;  // DENSE block (else: decode target)
+};
+template <>
+struct Payload<8> {
+    uint32_t q[2], s[2];
+    u32x4_t w0, w1;  // DENSE blocks of sub-steps 0, 1 (else: decode targets)
+};
+
+// Issue the loads of one strip-panel and step the cursor past it.  Magnitudes and signs are loaded by
+// every lane (a lane without a UNIFIED block reads a valid address of the same tile and the value is
+// dropped when decoding), so at least kPayloadLoads<B> vector-memory instructions are issued per panel;
+// DENSE blocks are loaded by the lanes that have one.
+template <int B>
+constexpr int kPayloadLoads = B == 16 ? 1 : 4;
+
+template <int B>
+__device__ inline void issue_payload(StripCursor &c, const PanelMasks<B> &m, Payload<B> &pay)
+{
+    constexpr int S = 16 / B;
+    constexpr uint32_t mag_off = kTilePanels * 2u * S * 8u;
+    // last valid payload index of the tile (a tile without UNIFIED blocks: its masks are read instead)
+    const uint32_t ulast = c.nU ? c.nU - 1u : 0u;
+    const uint32_t ubase = c.nU ? mag_off : 0u;
+    if constexpr (B == 16) {
+        uint32_t rk = c.ru + mbcnt64(m.u[0]);
+        rk = rk < ulast ? rk : ulast;
+        pay.rec = *(g_cu32 *)(c.tile + ubase + 4u * rk);
+        if (__builtin_amdgcn_inverse_ballot_w64(m.d[0])) {
+            g_cu32x4 *d = (g_cu32x4 *)(c.tile + c.dense_off + 32u * (c.rd + mbcnt64(m.d[0])));
+            pay.w0 = d[0];
+            pay.w1 = d[1];
+        }
+        c.ru += uint32_t(__popcll(m.u[0]));
+        c.rd += uint32_t(__popcll(m.d[0]));
+    } else {
+        const uint32_t sbase = c.nU ? c.sign_off : 0u;
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            uint32_t rk = c.ru + mbcnt64(m.u[j]);
+            rk = rk < ulast ? rk : ulast;
+            pay.q[j] = *(g_cu16 *)(c.tile + ubase + 2u * rk);
+            pay.s[j] = *(g_cu8 *)(c.tile + sbase + rk);
+            if (__builtin_amdgcn_inverse_ballot_w64(m.d[j])) {
+                const u32x4_t d = *(g_cu32x4 *)(c.tile + c.dense_off + 16u * (c.rd + mbcnt64(m.d[j])));
+                if (j == 0)
+                    pay.w0 = d;
+                else
+                    pay.w1 = d;
+            }
+            c.ru += uint32_t(__popcll(m.u[j]));
+            c.rd += uint32_t(__popcll(m.d[j]));
+        }
+    }
+}
+
+// Loaded payload -> the lane's 16 weights of the panel as two MFMA B-operands (w0: k = 16 g .. + 7,
+// w1: the next 8).
+template <int B>
+__device__ inline void decode_payload(const PanelMasks<B> &m, Payload<B> &pay)
+{
+    if constexpr (B == 16) {
+        if (!__builtin_amdgcn_inverse_ballot_w64(m.d[0])) {
+            // record (pack_record16): (rec << d) has the signs of elements 2 d, 2 d + 1 at bits 15, 31
+            const uint32_t rc = __builtin_amdgcn_inverse_ballot_w64(m.u[0]) ? pay.rec : 0u;
+            const uint32_t qq = __builtin_amdgcn_perm(rc, rc, 0x02000200u);
+            pay.w0.x = qq | (rc & 0x80008000u);
+            pay.w0.y = qq | ((rc << 1) & 0x80008000u);
+            pay.w0.z = qq | ((rc << 2) & 0x80008000u);
+            pay.w0.w = qq | ((rc << 3) & 0x80008000u);
+            pay.w1.x = qq | ((rc << 4) & 0x80008000u);
+            pay.w1.y = qq | ((rc << 5) & 0x80008000u);
+            pay.w1.z = qq | ((rc << 6) & 0x80008000u);
+            pay.w1.w = qq | ((rc << 7) & 0x80008000u);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16 / B; ++j) {
+            if (!__builtin_amdgcn_inverse_ballot_w64(m.d[j])) {
+                const bool uni = __builtin_amdgcn_inverse_ballot_w64(m.u[j]);
+                uint32_t w[4];
+                decode_block_bf16<8>(uni ? pay.q[j] : 0u, uni ? pay.s[j] : 0u, w);
+                const u32x4_t v = {w[0], w[1], w[2], w[3]};
+                if (j == 0)
+                    pay.w0 = v;
+                else
+                    pay.w1 = v;
+            }
+        }
+    }
+}
+
+#ifdef MUW_PROFILE_TILE
+// Timing build only: clock ticks per wave spent in the phases of a step, summed over all waves.
+__device__ unsigned long long g_tile_prof[8];
+#define TPROF_MARK(i) do { const uint32_t t_ = uint32_t(__builtin_amdgcn_s_memtime()); tprof[i] += t_ - tprof_t; tprof_t = t_; } while (0)
+#else
+#define TPROF_MARK(i) do { } while (0)
+#endif
+
+struct PipeArgs {
+    const uint8_t *blob;
+    const uint16_t *X;
+    void *Y;
+    int32_t M, ydtype;
+    int64_t ldx, ldy;
+    int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
+    float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
+};
+
+// Macro tile TM x 128 x 64, 4 waves 2 x 2 (wave tile TM/2 x 64).  Two of the eight strips of the tile
+// are a wave's decode duty.
+template <int B, int TM>
+__global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
+{
+    constexpr int MB = TM / 32;        // 16-row blocks per wave (two waves along M)
+    constexpr int NA = TM / 32;        // activation DMA instructions per wave and step (8 rows of 128 bytes each)
+    constexpr int ABYTES = TM * 128;   // one activation buffer
+    constexpr int BBYTES = kTN * 128;  // one weight buffer
+    __shared__ __attribute__((aligned(16))) uint8_t A_lds[3][ABYTES];
+    __shared__ __attribute__((aligned(16))) uint4 B_lds[2][kTN * 8];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = int64_t(blockIdx.y) * TM, n0 = int64_t(blockIdx.x) * kTN;
+    const int kp_lo = int(blockIdx.z) * a.kp_per;  // a multiple of the tile length (hence even)
+    const int kp_hi = kp_lo + a.kp_per < int(L.KP) ? kp_lo + a.kp_per : int(L.KP);
+
+    // ---- activation DMA: instruction i of this wave fills LDS rows 8 (wave NA + i) .. + 7; lane l is
+    //      16-byte slot (row, l % 8) and fetches the chunk that the swizzle stores there
+    uint32_t avoff[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int row = 8 * (wave * NA + i) + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        int64_t m = m0 + row;
+        if (m >= a.M) m = a.M - 1;  // rows past the end compute values that are never stored
+        avoff[i] = uint32_t((m * a.ldx + chunk * 8) * 2);
+    }
+    auto issue_a = [&](int kp, int buf) {
+        const uint64_t xk = reinterpret_cast<uint64_t>(a.X) + uint64_t(kp) * (kPanelK * 2);
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
+                                             (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+    };
+    // operand reads: row = 16 x block + r, chunk 2 g + h sits at slot (2 g + h) ^ ((r >> 1) & 7)
+    const uint32_t a_lds0 = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint8_t *)A_lds[0]));
+    const uint32_t b_lds0 = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint4 *)B_lds[0]));
+    uint32_t aaddr[2], baddr[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t slot = uint32_t(((2 * g + h) ^ ((r >> 1) & 7)) * 16);
+        aaddr[h] = a_lds0 + uint32_t((wm * (TM / 2) + r) * 128) + slot;
+        baddr[h] = b_lds0 + uint32_t((wn * 64 + r) * 128) + slot;
+    }
+
+    // ---- decode duty: strips 2 wave, 2 wave + 1 of the tile's eight
+    const int64_t sid0 = n0 / kStripRows + wave * 2;
+    StripCursor cur[2];
+    uint64_t ptile[2][2];  // [step parity][strip]: tile stream the fetched payload belongs to (0: none)
+    c_u32 *dirw = (c_u32 *)(a.blob + L.dir_off);
+    auto dir_entry = [&](int j, int kt) -> c_u32 * {
+        int64_t sid = sid0 + j;
+        if (sid >= L.NS) sid = 0;  // (loads must go somewhere valid; the result is zeroed when decoding)
+        return dirw + (sid * L.KT + kt) * 2;
+    };
+    auto tile_address = [&](uint32_t off16) -> uint64_t {
+        return reinterpret_cast<uint64_t>(a.blob) + L.streams_off + uint64_t(off16) * 16u;
+    };
+    // (`sink`: LDS bytes that the next activation DMA of this wave overwrites)
+    auto open_tile = [&](int j, int kt, bool first, uint8_t *sink) {
+        cur[j].live = sid0 + j < L.NS;
+        uint32_t off16, cnt;
+        if (first) {
+            c_u32 *e = dir_entry(j, kt);
+            off16 = e[0];
+            cnt = e[1];
+            if (kt + 1 < int(L.KT)) {
+                cur[j].next_off16 = e[2];  // (the strip's entries are consecutive)
+                cur[j].next_cnt = e[3];
+            }
+        } else {
+            off16 = cur[j].next_off16;
+            cnt = cur[j].next_cnt;
+            cur[j].next_off16 = cur[j].next2_off16;
+            cur[j].next_cnt = cur[j].next2_cnt;
+        }
+        if (kt + 1 < int(L.KT)) {
+            // bring the mask lines of the next tile stream into the cache (lanes 0 .. 3: 64 bytes apart)
+            const uint64_t nt = tile_address(cur[j].next_off16);
+            if (lane < 4)
+                __builtin_amdgcn_global_load_lds((global_void_t *)(nt + uint32_t(lane) * 64u), (lds_void_t *)sink, 4, 0, 0);
+        }
+        if (kt + 2 < int(L.KT)) {
+            c_u32 *e = dir_entry(j, kt + 2);
+            cur[j].next2_off16 = e[0];
+            cur[j].next2_cnt = e[1];
+        }
+        const uint32_t nU = cnt & 0xffffu;
+        constexpr uint32_t mag_off = kTilePanels * 2u * (16 / B) * 8u;
+        cur[j].tile = tile_address(off16);
+        cur[j].nU = nU;
+        cur[j].sign_off = mag_off + nU * 2u;
+        cur[j].dense_off = B == 16 ? mag_off + ((nU * 4u + 15u) & ~15u)
+                                   : (cur[j].sign_off + (nU * uint32_t(B) + 7u) / 8u + 15u) & ~15u;
+        cur[j].ru = cur[j].rd = 0;
+    };
+    auto open_tiles = [&](int kp, bool first, int next_abuf) {
+        if (kp % kTilePanels == 0) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                open_tile(j, kp / kTilePanels, first, A_lds[next_abuf] + wave * NA * 1024);
+        }
+    };
+
+    f32x4 acc[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc[mb][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    Payload<B> pay[2][2];  // [step parity][strip]
+    PanelMasks<B> mf[2];   // masks of the panel whose payload is fetched next (loaded one step ahead)
+    auto fetch = [&](const PanelMasks<B> (&m)[2], Payload<B> (&dst)[2], uint64_t (&dst_tile)[2]) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            dst_tile[j] = cur[j].live ? cur[j].tile : 0;
+            issue_payload<B>(cur[j], m[j], dst[j]);
+        }
+    };
+    auto decode_to_lds = [&](const PanelMasks<B> (&m)[2], Payload<B> (&src)[2], const uint64_t (&src_tile)[2], int buf) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (src_tile[j])
+                decode_payload<B>(m[j], src[j]);
+            else
+                src[j].w0 = src[j].w1 = u32x4_t{0, 0, 0, 0};
+            const int row = (2 * wave + j) * 16 + r;
+            B_lds[buf][swz(row, 2 * g)] = make_uint4(src[j].w0.x, src[j].w0.y, src[j].w0.z, src[j].w0.w);
+            B_lds[buf][swz(row, 2 * g + 1)] = make_uint4(src[j].w1.x, src[j].w1.y, src[j].w1.z, src[j].w1.w);
+        }
+    };
+    // End of a step: everything this wave issued in EARLIER steps has landed (the activation DMA of the
+    // next step among it), its LDS writes are done; then everyone's.  A full step issues NA DMA and at
+    // least 2 kPayloadLoads<B> payload instructions, which may stay in flight.
+    auto end_of_step = [&](bool full) {
+        if (full)
+            wait_vmcnt_imm<NA + 2 * kPayloadLoads<B>>();
+        else
+            wait_vmcnt_imm<0>();
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
+#ifdef MUW_PROFILE_TILE
+    uint32_t tprof[6] = {0, 0, 0, 0, 0, 0};
+    uint32_t tprof_t = uint32_t(__builtin_amdgcn_s_memtime());
+#endif
+    int abuf = 0;  // activation buffer of the current step (the DMA runs two steps ahead)
+    // One 64-k step kp with weight buffer and payload set PAR = kp % 2.
+    auto step = [&](int kp, auto par) {
+        constexpr int PAR = decltype(par)::value;
+        const bool full = kp + 2 < kp_hi, more = kp + 1 < kp_hi;
+        PanelMasks<B> md[2];
+        const int next_abuf = abuf >= 1 ? abuf - 1 : 2;
+        if (full) fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2 (mf: loaded during the previous step)
+        if (kp + 3 < kp_hi) {
+            open_tiles(kp + 3, false, next_abuf);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, (kp + 3) % kTilePanels, mf[j]);
+        }
+        if (full) issue_a(kp + 2, next_abuf);
+        if (more) {  // masks of the panel decoded in this step, again (a scalar-cache hit)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
+        }
+        TPROF_MARK(0);  // DMA, payload and mask loads issued
+        const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
+        // B fragments of this step (8 reads), first A fragments
+        u32x4_t bf[4][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bf[0][h] = lds_read_b128_at<PAR * BBYTES + 0 * 2048>(baddr[h]);
+            bf[1][h] = lds_read_b128_at<PAR * BBYTES + 1 * 2048>(baddr[h]);
+            bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
+            bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
+        }
+        u32x4_t af[2][2];
+        af[0][0] = lds_read_b128_at<0>(a0);
+        af[0][1] = lds_read_b128_at<0>(a1);
+        asm volatile("s_waitcnt lgkmcnt(2)"
+                     : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
+                       "+v"(bf[2][1]), "+v"(bf[3][1]));
+        TPROF_MARK(1);  // B fragment reads
+        if (more) decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
+        TPROF_MARK(2);  // decode (waits for the payload) and LDS writes
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int c = mb & 1;
+            if (mb + 1 < MB) {
+                // (the offset is an immediate of the instruction: spell the cases out)
+                auto rd = [&](auto mbc) {
+                    constexpr int OFF = decltype(mbc)::value * 2048;
+                    af[c ^ 1][0] = lds_read_b128_at<OFF>(a0);
+                    af[c ^ 1][1] = lds_read_b128_at<OFF>(a1);
+                };
+                if (mb == 0) rd(std::integral_constant<int, 1>{});
+                if (mb == 1) rd(std::integral_constant<int, 2>{});
+                if (mb == 2) rd(std::integral_constant<int, 3>{});
+                if (mb == 3) rd(std::integral_constant<int, 4 % MB>{});
+                if (mb == 4) rd(std::integral_constant<int, 5 % MB>{});
+                if (mb == 5) rd(std::integral_constant<int, 6 % MB>{});
+                if (mb == 6) rd(std::integral_constant<int, 7 % MB>{});
+                asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[c][0]), "+v"(af[c][1]));
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[c][0]), "+v"(af[c][1]));
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    mfma_acc(acc[mb][s], af[c][h], bf[s][h]);
+        }
+        abuf = abuf == 2 ? 0 : abuf + 1;
+        TPROF_MARK(3);  // MFMA loop
+        end_of_step(full);
+        TPROF_MARK(4);  // end-of-step waits and barrier
+    };
+
+    if (kp_lo < kp_hi) {
+        {  // (kp_lo is the first panel of a tile: splits cover whole tiles)
+            PanelMasks<B> m0[2], m1[2];
+            open_tiles(kp_lo, true, 0);
+            issue_a(kp_lo, 0);
+            if (kp_lo + 1 < kp_hi) issue_a(kp_lo + 1, 1);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 0, m0[j]);
+            fetch(m0, pay[0], ptile[0]);
+            if (kp_lo + 1 < kp_hi) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 1, m1[j]);
+                fetch(m1, pay[1], ptile[1]);
+            }
+            if (kp_lo + 2 < kp_hi) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 2, mf[j]);
+            }
+            decode_to_lds(m0, pay[0], ptile[0], 0);
+        }
+        end_of_step(false);
+        int kp = kp_lo;
+        for (; kp + 1 < kp_hi; kp += 2) {
+            step(kp, std::integral_constant<int, 0>{});
+            step(kp + 1, std::integral_constant<int, 1>{});
+        }
+        if (kp < kp_hi) step(kp, std::integral_constant<int, 0>{});
+    }
+#ifdef MUW_PROFILE_TILE
+    if (lane == 0)
+        for (int i = 0; i < 6; ++i) atomicAdd(&g_tile_prof[i], (unsigned long long)tprof[i]);
+#endif
+
+    // ---- epilogue: lane holds Y[m = 4 g + v][n = r] of each 16 x 16 block
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int64_t n = n0 + wn * 64 + s * 16 + r;
+            if (n >= L.N) continue;
+            const int64_t mq = m0 + wm * (TM / 2) + mb * 16 + 4 * g;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t m = mq + v;
+                if (m >= a.M) continue;
+                if (a.Ypart)
+                    a.Ypart[(int64_t(blockIdx.z) * a.M + m) * L.N + n] = acc[mb][s][v];
+                else if (a.ydtype == MUW_F32)
+                    static_cast<float *>(a.Y)[m * a.ldy + n] = acc[mb][s][v];
+                else
+                    static_cast<uint16_t *>(a.Y)[m * a.ldy + n] = f32_to_bf16_rne(acc[mb][s][v]);
+            }
+        }
+}
+
+// The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels.
+template <int B>
+bool pipe_applicable(const TileGemmArgs &a, const Layout &L)
+{
+    if (B != 8 && B != 16) return false;
+    if (L.K % kPanelK != 0 || a.M < 1 || a.M >= (int64_t(1) << 30)) return false;
+    return uint64_t(a.M) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);  // 32-bit DMA offsets
+}
+
+template <int B>
+muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    if constexpr (B == 8 || B == 16) {
+        // 128-row tiles: two workgroups per compute unit hide each other's waits.  (The 256-row
+        // instantiation needs more than 256 registers per lane; the compiler then parks loaded payload
+        // in the accumulation registers, which forces a wait right after the loads are issued, and it
+        // measured slower.)
+        const int tm = 128;
+        int splits = tile_splits(L, t.M, tm);
+        if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
+        const int64_t kt_per = (L.KT + splits - 1) / splits;
+        splits = int((L.KT + kt_per - 1) / kt_per);
+        PipeArgs a{};
+        a.blob = t.blob;
+        a.X = t.X;
+        a.Y = t.Y;
+        a.M = int32_t(t.M);
+        a.ydtype = t.ydtype;
+        a.ldx = t.ldx;
+        a.ldy = t.ldy;
+        a.kp_per = int32_t(kt_per * kTilePanels);
+        a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
+        const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
+        dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
+        k_pipe_gemm_bf16<B, 128><<<grid, 256, 0, st>>>(a, L);
+        if (splits > 1) {
+            const int64_t total = t.M * L.N;
+            k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, t.M, L.N, t.Y, t.ldy,
+                                                                        t.ydtype, 0);
+        }
+        return hip_status(hipGetLastError());
+    } else {
+        return MUW_EUNSUPPORTED;
+    }
+}
