@@ -41,15 +41,6 @@ __device__ inline u32x4_t lds_read_b128_at(uint32_t addr)
     return v;
 }
 
-// acc += a * b with the accumulator pinned in the accumulation registers: left to the compiler, the 128
-// accumulators of a 256-row tile take the ordinary registers and everything else is shuffled through
-// the accumulation registers by copies (which also forces early waits on loaded values).  Dependent
-// accumulations are at least four MFMAs apart in this file, so no wait states are missing.
-__device__ inline void mfma_acc(f32x4 &acc, const u32x4_t &a, const u32x4_t &b)
-{
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
 // Scalar state of one strip of the decode duty: where its current tile stream is and how many blocks
 // of it the panels before the next one hold.
 struct StripCursor {
@@ -93,6 +84,34 @@ struct Payload<8> {
     u32x4_t w0, w1;  // DENSE blocks of sub-steps 0, 1 (else: decode targets)
 };
 
+// Payload loads are inline assembly: the compiler's own wait insertion waits for ALL vector-memory
+// operations before the first use of a value loaded in an earlier loop iteration, i.e. also for the
+// loads just issued for later steps.  The loaded registers are tied to one counted wait right before
+// they are decoded (wait_payload below).  base: scalar address of the tile stream, off: byte offset.
+__device__ inline void load_u16_at(uint32_t &dst, uint64_t base, uint32_t off)
+{
+    asm volatile("global_load_ushort %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base));
+}
+__device__ inline void load_u8_at(uint32_t &dst, uint64_t base, uint32_t off)
+{
+    asm volatile("global_load_ubyte %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base));
+}
+__device__ inline void load_u32_at(uint32_t &dst, uint64_t base, uint32_t off)
+{
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base));
+}
+// (in/out: lanes switched off by the surrounding branch keep what they had)
+__device__ inline void load_b128_at(u32x4_t &dst, uint64_t base, uint32_t off)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(dst) : "v"(off), "s"(base));
+}
+__device__ inline void load_2xb128_at(u32x4_t &d0, u32x4_t &d1, uint64_t base, uint32_t off)
+{
+    asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dwordx4 %1, %2, %3 offset:16"
+                 : "+v"(d0), "+v"(d1)
+                 : "v"(off), "s"(base));
+}
+
 // Issue the loads of one strip-panel and step the cursor past it.  Magnitudes and signs are loaded by
 // every lane (a lane without a UNIFIED block reads a valid address of the same tile and the value is
 // dropped when decoding), so at least kPayloadLoads<B> vector-memory instructions are issued per panel;
@@ -111,12 +130,9 @@ __device__ inline void issue_payload(StripCursor &c, const PanelMasks<B> &m, Pay
     if constexpr (B == 16) {
         uint32_t rk = c.ru + mbcnt64(m.u[0]);
         rk = rk < ulast ? rk : ulast;
-        pay.rec = *(g_cu32 *)(c.tile + ubase + 4u * rk);
-        if (__builtin_amdgcn_inverse_ballot_w64(m.d[0])) {
-            g_cu32x4 *d = (g_cu32x4 *)(c.tile + c.dense_off + 32u * (c.rd + mbcnt64(m.d[0])));
-            pay.w0 = d[0];
-            pay.w1 = d[1];
-        }
+        load_u32_at(pay.rec, c.tile, ubase + 4u * rk);
+        if (__builtin_amdgcn_inverse_ballot_w64(m.d[0]))
+            load_2xb128_at(pay.w0, pay.w1, c.tile, c.dense_off + 32u * (c.rd + mbcnt64(m.d[0])));
         c.ru += uint32_t(__popcll(m.u[0]));
         c.rd += uint32_t(__popcll(m.d[0]));
     } else {
@@ -125,18 +141,32 @@ __device__ inline void issue_payload(StripCursor &c, const PanelMasks<B> &m, Pay
         for (int j = 0; j < S; ++j) {
             uint32_t rk = c.ru + mbcnt64(m.u[j]);
             rk = rk < ulast ? rk : ulast;
-            pay.q[j] = *(g_cu16 *)(c.tile + ubase + 2u * rk);
-            pay.s[j] = *(g_cu8 *)(c.tile + sbase + rk);
-            if (__builtin_amdgcn_inverse_ballot_w64(m.d[j])) {
-                const u32x4_t d = *(g_cu32x4 *)(c.tile + c.dense_off + 16u * (c.rd + mbcnt64(m.d[j])));
-                if (j == 0)
-                    pay.w0 = d;
-                else
-                    pay.w1 = d;
-            }
+            load_u16_at(pay.q[j], c.tile, ubase + 2u * rk);
+            load_u8_at(pay.s[j], c.tile, sbase + rk);
+            if (__builtin_amdgcn_inverse_ballot_w64(m.d[j]))
+                load_b128_at(j == 0 ? pay.w0 : pay.w1, c.tile, c.dense_off + 16u * (c.rd + mbcnt64(m.d[j])));
             c.ru += uint32_t(__popcll(m.u[j]));
             c.rd += uint32_t(__popcll(m.d[j]));
         }
+    }
+}
+
+// Wait until at most N vector-memory operations are in flight; the payload registers of two strips are
+// tied to the wait so that no use of them can be scheduled before it.
+template <int N, int B>
+__device__ inline void wait_payload(Payload<B> (&p)[2])
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    constexpr int IMM = (N & 15) | ((N >> 4) << 14) | 0x0f70;
+    if constexpr (B == 16) {
+        asm volatile("s_waitcnt %6"
+                     : "+v"(p[0].rec), "+v"(p[0].w0), "+v"(p[0].w1), "+v"(p[1].rec), "+v"(p[1].w0), "+v"(p[1].w1)
+                     : "n"(IMM));
+    } else {
+        asm volatile("s_waitcnt %12"
+                     : "+v"(p[0].q[0]), "+v"(p[0].q[1]), "+v"(p[0].s[0]), "+v"(p[0].s[1]), "+v"(p[0].w0), "+v"(p[0].w1),
+                       "+v"(p[1].q[0]), "+v"(p[1].q[1]), "+v"(p[1].s[0]), "+v"(p[1].s[1]), "+v"(p[1].w0), "+v"(p[1].w1)
+                     : "n"(IMM));
     }
 }
 
@@ -345,14 +375,17 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
     uint32_t tprof_t = uint32_t(__builtin_amdgcn_s_memtime());
 #endif
     int abuf = 0;  // activation buffer of the current step (the DMA runs two steps ahead)
-    // One 64-k step kp with weight buffer and payload set PAR = kp % 2.
-    auto step = [&](int kp, auto par) {
+    // One 64-k step kp with weight buffer and payload set PAR = kp % 2.  STEADY: at least three more
+    // steps follow, so every prefetch of the step happens (known at compile time: a loaded value that
+    // merges with an old one at the end of a branch is copied there, and the copy waits for the load).
+    auto step = [&](int kp, auto par, auto steady) {
         constexpr int PAR = decltype(par)::value;
-        const bool full = kp + 2 < kp_hi, more = kp + 1 < kp_hi;
+        constexpr bool STEADY = decltype(steady)::value;
+        const bool full = STEADY || kp + 2 < kp_hi, more = STEADY || kp + 1 < kp_hi;
         PanelMasks<B> md[2];
         const int next_abuf = abuf >= 1 ? abuf - 1 : 2;
         if (full) fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2 (mf: loaded during the previous step)
-        if (kp + 3 < kp_hi) {
+        if (STEADY || kp + 3 < kp_hi) {
             open_tiles(kp + 3, false, next_abuf);
 #pragma unroll
             for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, (kp + 3) % kTilePanels, mf[j]);
@@ -381,7 +414,15 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
                      : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
                        "+v"(bf[2][1]), "+v"(bf[3][1]));
         TPROF_MARK(1);  // B fragment reads
-        if (more) decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
+        if (more) {
+            // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
+            // at least the activation DMA of two steps and the payload loads of this one.
+            if (STEADY)
+                wait_payload<2 * NA + 2 * kPayloadLoads<B>>(pay[PAR ^ 1]);
+            else
+                wait_payload<0>(pay[PAR ^ 1]);
+            decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
+        }
         TPROF_MARK(2);  // decode (waits for the payload) and LDS writes
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -408,7 +449,9 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    mfma_acc(acc[mb][s], af[c][h], bf[s][h]);
+                    acc[mb][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[c][h]),
+                                                                         __builtin_bit_cast(bf16x8, bf[s][h]),
+                                                                         acc[mb][s], 0, 0, 0);
         }
         abuf = abuf == 2 ? 0 : abuf + 1;
         TPROF_MARK(3);  // MFMA loop
@@ -434,15 +477,20 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
 #pragma unroll
                 for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 2, mf[j]);
             }
+            wait_payload<0>(pay[0]);
             decode_to_lds(m0, pay[0], ptile[0], 0);
         }
         end_of_step(false);
         int kp = kp_lo;
-        for (; kp + 1 < kp_hi; kp += 2) {
-            step(kp, std::integral_constant<int, 0>{});
-            step(kp + 1, std::integral_constant<int, 1>{});
+        for (; kp + 4 < kp_hi; kp += 2) {
+            step(kp, std::integral_constant<int, 0>{}, std::true_type{});
+            step(kp + 1, std::integral_constant<int, 1>{}, std::true_type{});
         }
-        if (kp < kp_hi) step(kp, std::integral_constant<int, 0>{});
+        for (; kp + 1 < kp_hi; kp += 2) {
+            step(kp, std::integral_constant<int, 0>{}, std::false_type{});
+            step(kp + 1, std::integral_constant<int, 1>{}, std::false_type{});
+        }
+        if (kp < kp_hi) step(kp, std::integral_constant<int, 0>{}, std::false_type{});
     }
 #ifdef MUW_PROFILE_TILE
     if (lane == 0)
