@@ -2,11 +2,12 @@
 //
 // Linear layers with K a multiple of 64 and B = 8 or 16: the LDS-tiled MFMA GEMM of muw_mfma.hip, software
 // pipelined (paper Sec. 3.2: the layer is a blocked GEMM whose weight tile is decoded on the fly).
-//   - the activation tile is triple buffered in LDS and filled by global_load_lds two steps ahead;
+//   - the activation tile is double buffered in LDS and filled by global_load_lds one step ahead;
 //   - the compressed payload of a step is gathered into registers two steps ahead (payload index by
-//     v_mbcnt over masks in scalar registers).  Every wait on the scalar/LDS counter also waits for the
-//     scalar loads in flight, so those must hit a cache: the mask lines of a tile stream are touched by a
-//     small DMA one tile before its first scalar load, directory entries are loaded two tiles ahead;
+//     v_mbcnt over the panel masks).  Every wait on the scalar/LDS counter also waits for the scalar loads
+//     in flight, so the steady state has none that can miss: masks come through LDS by a small DMA three
+//     steps ahead (lane i reads dword i; v_readlane makes them scalar), directory entries are loaded two
+//     tiles ahead;
 //   - the payload of step t + 1 is decoded into the other weight buffer while the MFMAs of step t run;
 //   - one barrier per 64-k step.
 #pragma once
@@ -59,6 +60,7 @@ template <int B>
 struct PanelMasks {
     uint64_t u[16 / B], d[16 / B];
 };
+// Scalar load of a panel's masks (prologue and tail only).
 template <int B>
 __device__ inline void load_panel_masks(uint64_t tile, int p, PanelMasks<B> &m)
 {
@@ -68,6 +70,39 @@ __device__ inline void load_panel_masks(uint64_t tile, int p, PanelMasks<B> &m)
     for (int j = 0; j < S; ++j) {
         m.u[j] = src[j];
         m.d[j] = src[S + j];
+    }
+}
+// DMA of a panel's masks (2 S masks = 4 S dwords) into LDS, and the read that gives lane i (mod 4 S)
+// dword i.  (The read is inline assembly like the operand reads: the compiler would wait for every
+// pending vector-memory operation before an ordinary load of DMA-filled LDS.)
+template <int B>
+__device__ inline void issue_mask_dma(uint64_t tile, int p, int lane, uint8_t *slot)
+{
+    constexpr int S = 16 / B;
+    if (lane < 4 * S)
+        __builtin_amdgcn_global_load_lds((global_void_t *)(tile + uint32_t(p) * (2u * S * 8u) + uint32_t(lane) * 4u),
+                                         (lds_void_t *)slot, 4, 0, 0);
+}
+template <int B>
+__device__ inline uint32_t read_mask_lanes(const uint8_t *slot, int lane)
+{
+    constexpr int S = 16 / B;
+    const uint32_t addr = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint8_t *)slot)) +
+                          uint32_t(lane & (4 * S - 1)) * 4u;
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+template <int B>
+__device__ inline void masks_from_lanes(uint32_t raw, PanelMasks<B> &m)
+{
+    constexpr int S = 16 / B;
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        const uint32_t ulo = __builtin_amdgcn_readlane(raw, 2 * j), uhi = __builtin_amdgcn_readlane(raw, 2 * j + 1);
+        const uint32_t dlo = __builtin_amdgcn_readlane(raw, 2 * (S + j)), dhi = __builtin_amdgcn_readlane(raw, 2 * (S + j) + 1);
+        m.u[j] = (uint64_t(uhi) << 32) | ulo;
+        m.d[j] = (uint64_t(dhi) << 32) | dlo;
     }
 }
 
@@ -233,8 +268,9 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
     constexpr int NA = TM / 32;        // activation DMA instructions per wave and step (8 rows of 128 bytes each)
     constexpr int ABYTES = TM * 128;   // one activation buffer
     constexpr int BBYTES = kTN * 128;  // one weight buffer
-    __shared__ __attribute__((aligned(16))) uint8_t A_lds[3][ABYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t A_lds[2][ABYTES];
     __shared__ __attribute__((aligned(16))) uint4 B_lds[2][kTN * 8];
+    __shared__ __attribute__((aligned(16))) uint8_t M_lds[4][3][2][32];  // [wave][step % 3][strip]: panel masks
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -286,8 +322,7 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
     auto tile_address = [&](uint32_t off16) -> uint64_t {
         return reinterpret_cast<uint64_t>(a.blob) + L.streams_off + uint64_t(off16) * 16u;
     };
-    // (`sink`: LDS bytes that the next activation DMA of this wave overwrites)
-    auto open_tile = [&](int j, int kt, bool first, uint8_t *sink) {
+    auto open_tile = [&](int j, int kt, bool first) {
         cur[j].live = sid0 + j < L.NS;
         uint32_t off16, cnt;
         if (first) {
@@ -304,12 +339,6 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
             cur[j].next_off16 = cur[j].next2_off16;
             cur[j].next_cnt = cur[j].next2_cnt;
         }
-        if (kt + 1 < int(L.KT)) {
-            // bring the mask lines of the next tile stream into the cache (lanes 0 .. 3: 64 bytes apart)
-            const uint64_t nt = tile_address(cur[j].next_off16);
-            if (lane < 4)
-                __builtin_amdgcn_global_load_lds((global_void_t *)(nt + uint32_t(lane) * 64u), (lds_void_t *)sink, 4, 0, 0);
-        }
         if (kt + 2 < int(L.KT)) {
             c_u32 *e = dir_entry(j, kt + 2);
             cur[j].next2_off16 = e[0];
@@ -324,11 +353,10 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
                                    : (cur[j].sign_off + (nU * uint32_t(B) + 7u) / 8u + 15u) & ~15u;
         cur[j].ru = cur[j].rd = 0;
     };
-    auto open_tiles = [&](int kp, bool first, int next_abuf) {
+    auto open_tiles = [&](int kp, bool first) {
         if (kp % kTilePanels == 0) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                open_tile(j, kp / kTilePanels, first, A_lds[next_abuf] + wave * NA * 1024);
+            for (int j = 0; j < 2; ++j) open_tile(j, kp / kTilePanels, first);
         }
     };
 
@@ -339,7 +367,9 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         for (int s = 0; s < 4; ++s) acc[mb][s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     Payload<B> pay[2][2];  // [step parity][strip]
-    PanelMasks<B> mf[2];   // masks of the panel whose payload is fetched next (loaded one step ahead)
+    auto peek_tile = [&](int j, int kp) -> uint64_t {  // tile stream of panel kp, one step before it is opened
+        return kp % kTilePanels == 0 ? tile_address(cur[j].next_off16) : cur[j].tile;
+    };
     auto fetch = [&](const PanelMasks<B> (&m)[2], Payload<B> (&dst)[2], uint64_t (&dst_tile)[2]) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -359,12 +389,12 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
             B_lds[buf][swz(row, 2 * g + 1)] = make_uint4(src[j].w1.x, src[j].w1.y, src[j].w1.z, src[j].w1.w);
         }
     };
-    // End of a step: everything this wave issued in EARLIER steps has landed (the activation DMA of the
-    // next step among it), its LDS writes are done; then everyone's.  A full step issues NA DMA and at
-    // least 2 kPayloadLoads<B> payload instructions, which may stay in flight.
-    auto end_of_step = [&](bool full) {
-        if (full)
-            wait_vmcnt_imm<NA + 2 * kPayloadLoads<B>>();
+    // End of a step: this wave's activation and mask DMA have landed (in the steady state they are
+    // issued before the step's payload loads, at least 2 kPayloadLoads<B>, which may stay in flight),
+    // its LDS writes are done; then everyone's.
+    auto end_of_step = [&](bool steady) {
+        if (steady)
+            wait_vmcnt_imm<2 * kPayloadLoads<B>>();
         else
             wait_vmcnt_imm<0>();
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -374,7 +404,6 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
     uint32_t tprof[6] = {0, 0, 0, 0, 0, 0};
     uint32_t tprof_t = uint32_t(__builtin_amdgcn_s_memtime());
 #endif
-    int abuf = 0;  // activation buffer of the current step (the DMA runs two steps ahead)
     // One 64-k step kp with weight buffer and payload set PAR = kp % 2.  STEADY: at least three more
     // steps follow, so every prefetch of the step happens (known at compile time: a loaded value that
     // merges with an old one at the end of a branch is copied there, and the copy waits for the load).
@@ -382,22 +411,44 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         constexpr int PAR = decltype(par)::value;
         constexpr bool STEADY = decltype(steady)::value;
         const bool full = STEADY || kp + 2 < kp_hi, more = STEADY || kp + 1 < kp_hi;
-        PanelMasks<B> md[2];
-        const int next_abuf = abuf >= 1 ? abuf - 1 : 2;
-        if (full) fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2 (mf: loaded during the previous step)
-        if (STEADY || kp + 3 < kp_hi) {
-            open_tiles(kp + 3, false, next_abuf);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, (kp + 3) % kTilePanels, mf[j]);
-        }
-        if (full) issue_a(kp + 2, next_abuf);
-        if (more) {  // masks of the panel decoded in this step, again (a scalar-cache hit)
+        PanelMasks<B> mf[2], md[2];
+        if constexpr (STEADY) {
+            issue_a(kp + 1, PAR ^ 1);
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
+                issue_mask_dma<B>(peek_tile(j, kp + 3), (kp + 3) % kTilePanels, lane, M_lds[wave][(kp + 3) % 3][j]);
+            // masks of the panels fetched and decoded in this step (their DMA landed before the last barrier)
+            uint32_t rf[2], rdm[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % 3][j], lane);
+                rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % 3][j], lane);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[1]), "+v"(rdm[0]), "+v"(rdm[1]));
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                masks_from_lanes<B>(rf[j], mf[j]);
+                masks_from_lanes<B>(rdm[j], md[j]);
+            }
+            fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2
+            open_tiles(kp + 3, false);
+        } else {
+            // tail (and short K ranges): scalar mask loads, waited for on the spot
+            if (more) issue_a(kp + 1, PAR ^ 1);
+            if (full) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
+                fetch(mf, pay[PAR], ptile[PAR]);
+            }
+            if (kp + 3 < kp_hi) open_tiles(kp + 3, false);
+            if (more) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
+            }
         }
         TPROF_MARK(0);  // DMA, payload and mask loads issued
-        const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
+        const uint32_t a0 = aaddr[0] + uint32_t(PAR) * ABYTES, a1 = aaddr[1] + uint32_t(PAR) * ABYTES;
         // B fragments of this step (8 reads), first A fragments
         u32x4_t bf[4][2];
 #pragma unroll
@@ -416,9 +467,9 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         TPROF_MARK(1);  // B fragment reads
         if (more) {
             // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
-            // at least the activation DMA of two steps and the payload loads of this one.
+            // at least the activation and mask DMA and the payload loads of this step.
             if (STEADY)
-                wait_payload<2 * NA + 2 * kPayloadLoads<B>>(pay[PAR ^ 1]);
+                wait_payload<NA + 2 + 2 * kPayloadLoads<B>>(pay[PAR ^ 1]);
             else
                 wait_payload<0>(pay[PAR ^ 1]);
             decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
@@ -453,18 +504,16 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
                                                                          __builtin_bit_cast(bf16x8, bf[s][h]),
                                                                          acc[mb][s], 0, 0, 0);
         }
-        abuf = abuf == 2 ? 0 : abuf + 1;
         TPROF_MARK(3);  // MFMA loop
-        end_of_step(full);
+        end_of_step(STEADY);
         TPROF_MARK(4);  // end-of-step waits and barrier
     };
 
     if (kp_lo < kp_hi) {
         {  // (kp_lo is the first panel of a tile: splits cover whole tiles)
             PanelMasks<B> m0[2], m1[2];
-            open_tiles(kp_lo, true, 0);
+            open_tiles(kp_lo, true);
             issue_a(kp_lo, 0);
-            if (kp_lo + 1 < kp_hi) issue_a(kp_lo + 1, 1);
 #pragma unroll
             for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 0, m0[j]);
             fetch(m0, pay[0], ptile[0]);
@@ -473,9 +522,12 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
                 for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 1, m1[j]);
                 fetch(m1, pay[1], ptile[1]);
             }
-            if (kp_lo + 2 < kp_hi) {
+            if (kp_lo + 4 < kp_hi) {  // the steady-state loop runs: masks of panels kp_lo + 1, + 2 through LDS
 #pragma unroll
-                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 2, mf[j]);
+                for (int j = 0; j < 2; ++j) {
+                    issue_mask_dma<B>(cur[j].tile, 1, lane, M_lds[wave][(kp_lo + 1) % 3][j]);
+                    issue_mask_dma<B>(cur[j].tile, 2, lane, M_lds[wave][(kp_lo + 2) % 3][j]);
+                }
             }
             wait_payload<0>(pay[0]);
             decode_to_lds(m0, pay[0], ptile[0], 0);
