@@ -2,10 +2,10 @@
 //
 // Linear layers with K a multiple of 64 and B = 8 or 16: the LDS-tiled MFMA GEMM of muw_mfma.hip, software
 // pipelined (paper Sec. 3.2: the layer is a blocked GEMM whose weight tile is decoded on the fly).
-//   - the activation tile is double buffered in LDS and filled by global_load_lds one step ahead;
+//   - the activation tile is triple buffered in LDS and filled by global_load_lds two steps ahead;
 //   - the compressed payload of a step is gathered into registers two steps ahead (payload index by
 //     v_mbcnt over the panel masks).  Every wait on the scalar/LDS counter also waits for the scalar loads
-//     in flight, so the steady state has none that can miss: masks come through LDS by a small DMA three
+//     in flight, so the steady state has none that can miss: masks come through LDS by a small DMA four
 //     steps ahead (lane i reads dword i; v_readlane makes them scalar), directory entries are loaded two
 //     tiles ahead;
 //   - the payload of step t + 1 is decoded into the other weight buffer while the MFMAs of step t run;
@@ -186,21 +186,18 @@ __device__ inline void issue_payload(StripCursor &c, const PanelMasks<B> &m, Pay
     }
 }
 
-// Wait until at most N vector-memory operations are in flight; the payload registers of two strips are
-// tied to the wait so that no use of them can be scheduled before it.
+// Wait until at most N vector-memory operations are in flight; the payload registers are tied to the
+// wait so that no use of them can be scheduled before it.
 template <int N, int B>
-__device__ inline void wait_payload(Payload<B> (&p)[2])
+__device__ inline void wait_payload(Payload<B> &p)
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     constexpr int IMM = (N & 15) | ((N >> 4) << 14) | 0x0f70;
     if constexpr (B == 16) {
-        asm volatile("s_waitcnt %6"
-                     : "+v"(p[0].rec), "+v"(p[0].w0), "+v"(p[0].w1), "+v"(p[1].rec), "+v"(p[1].w0), "+v"(p[1].w1)
-                     : "n"(IMM));
+        asm volatile("s_waitcnt %3" : "+v"(p.rec), "+v"(p.w0), "+v"(p.w1) : "n"(IMM));
     } else {
-        asm volatile("s_waitcnt %12"
-                     : "+v"(p[0].q[0]), "+v"(p[0].q[1]), "+v"(p[0].s[0]), "+v"(p[0].s[1]), "+v"(p[0].w0), "+v"(p[0].w1),
-                       "+v"(p[1].q[0]), "+v"(p[1].q[1]), "+v"(p[1].s[0]), "+v"(p[1].s[1]), "+v"(p[1].w0), "+v"(p[1].w1)
+        asm volatile("s_waitcnt %6"
+                     : "+v"(p.q[0]), "+v"(p.q[1]), "+v"(p.s[0]), "+v"(p.s[1]), "+v"(p.w0), "+v"(p.w1)
                      : "n"(IMM));
     }
 }
@@ -259,18 +256,23 @@ struct PipeArgs {
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
 };
 
-// Macro tile TM x 128 x 64, 4 waves 2 x 2 (wave tile TM/2 x 64).  Two of the eight strips of the tile
-// are a wave's decode duty.
-template <int B, int TM>
-__global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
+// Macro tile TM x 128 x 64, NW waves as NW/2 x 2, wave tile 64 x 64 (TM = 32 NW).  NS = 8 / NW of the
+// eight strips of the tile are a wave's decode duty: with 8 waves the decode of a strip is shared by 256
+// rows of activations.
+template <int B, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
 {
-    constexpr int MB = TM / 32;        // 16-row blocks per wave (two waves along M)
-    constexpr int NA = TM / 32;        // activation DMA instructions per wave and step (8 rows of 128 bytes each)
+    constexpr int TM = 32 * NW;
+    constexpr int NS = 8 / NW;         // strips decoded by a wave
+    constexpr int MB = 4;              // 16-row blocks per wave
+    constexpr int NA = 4;              // activation DMA instructions per wave and step (8 rows of 128 bytes each)
     constexpr int ABYTES = TM * 128;   // one activation buffer
     constexpr int BBYTES = kTN * 128;  // one weight buffer
-    __shared__ __attribute__((aligned(16))) uint8_t A_lds[2][ABYTES];
+    constexpr int NAB = NW == 8 ? 3 : 2;  // activation buffers (three fit only with one workgroup per compute unit)
+    constexpr int NMS = 4;             // mask slots
+    __shared__ __attribute__((aligned(16))) uint8_t A_lds[NAB][ABYTES];
     __shared__ __attribute__((aligned(16))) uint4 B_lds[2][kTN * 8];
-    __shared__ __attribute__((aligned(16))) uint8_t M_lds[4][3][2][32];  // [wave][step % 3][strip]: panel masks
+    __shared__ __attribute__((aligned(16))) uint8_t M_lds[NW][NMS][NS][32];  // [wave][step % 4][strip]: panel masks
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -305,14 +307,14 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const uint32_t slot = uint32_t(((2 * g + h) ^ ((r >> 1) & 7)) * 16);
-        aaddr[h] = a_lds0 + uint32_t((wm * (TM / 2) + r) * 128) + slot;
+        aaddr[h] = a_lds0 + uint32_t((wm * 64 + r) * 128) + slot;
         baddr[h] = b_lds0 + uint32_t((wn * 64 + r) * 128) + slot;
     }
 
-    // ---- decode duty: strips 2 wave, 2 wave + 1 of the tile's eight
-    const int64_t sid0 = n0 / kStripRows + wave * 2;
-    StripCursor cur[2];
-    uint64_t ptile[2][2];  // [step parity][strip]: tile stream the fetched payload belongs to (0: none)
+    // ---- decode duty: strips NS wave .. NS wave + NS - 1 of the tile's eight
+    const int64_t sid0 = n0 / kStripRows + wave * NS;
+    StripCursor cur[NS];
+    uint64_t ptile[2][NS];  // [step parity][strip]: tile stream the fetched payload belongs to (0: none)
     c_u32 *dirw = (c_u32 *)(a.blob + L.dir_off);
     auto dir_entry = [&](int j, int kt) -> c_u32 * {
         int64_t sid = sid0 + j;
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
     auto open_tiles = [&](int kp, bool first) {
         if (kp % kTilePanels == 0) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) open_tile(j, kp / kTilePanels, first);
+            for (int j = 0; j < NS; ++j) open_tile(j, kp / kTilePanels, first);
         }
     };
 
@@ -366,39 +368,43 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
 #pragma unroll
         for (int s = 0; s < 4; ++s) acc[mb][s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    Payload<B> pay[2][2];  // [step parity][strip]
-    auto peek_tile = [&](int j, int kp) -> uint64_t {  // tile stream of panel kp, one step before it is opened
-        return kp % kTilePanels == 0 ? tile_address(cur[j].next_off16) : cur[j].tile;
+    Payload<B> pay[2][NS];  // [step parity][strip]
+    // tile stream of panel kp while the cursor is still in the tile of panel kp - 2
+    auto peek_tile = [&](int j, int kp) -> uint64_t {
+        return kp / kTilePanels != (kp - 2) / kTilePanels ? tile_address(cur[j].next_off16) : cur[j].tile;
     };
-    auto fetch = [&](const PanelMasks<B> (&m)[2], Payload<B> (&dst)[2], uint64_t (&dst_tile)[2]) {
+    auto fetch = [&](const PanelMasks<B> (&m)[NS], Payload<B> (&dst)[NS], uint64_t (&dst_tile)[NS]) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NS; ++j) {
             dst_tile[j] = cur[j].live ? cur[j].tile : 0;
             issue_payload<B>(cur[j], m[j], dst[j]);
         }
     };
-    auto decode_to_lds = [&](const PanelMasks<B> (&m)[2], Payload<B> (&src)[2], const uint64_t (&src_tile)[2], int buf) {
+    auto decode_to_lds = [&](const PanelMasks<B> (&m)[NS], Payload<B> (&src)[NS], const uint64_t (&src_tile)[NS], int buf) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NS; ++j) {
             if (src_tile[j])
                 decode_payload<B>(m[j], src[j]);
             else
                 src[j].w0 = src[j].w1 = u32x4_t{0, 0, 0, 0};
-            const int row = (2 * wave + j) * 16 + r;
+            const int row = (NS * wave + j) * 16 + r;
             B_lds[buf][swz(row, 2 * g)] = make_uint4(src[j].w0.x, src[j].w0.y, src[j].w0.z, src[j].w0.w);
             B_lds[buf][swz(row, 2 * g + 1)] = make_uint4(src[j].w1.x, src[j].w1.y, src[j].w1.z, src[j].w1.w);
         }
     };
-    // End of a step: this wave's activation and mask DMA have landed (in the steady state they are
-    // issued before the step's payload loads, at least 2 kPayloadLoads<B>, which may stay in flight),
-    // its LDS writes are done; then everyone's.
+    // End of a step: everything this wave requested in EARLIER steps has landed (the activation tile of
+    // the next step and the masks of the next two among it; what a steady step requests itself -- NA
+    // activation DMAs, NS mask DMAs, at least NS kPayloadLoads<B> payload loads -- may stay in flight);
+    // its LDS writes are done; then everyone's.  (With two activation buffers the DMA runs one step
+    // ahead only and must land as well: it is issued before the payload loads.)
     auto end_of_step = [&](bool steady) {
         if (steady)
-            wait_vmcnt_imm<2 * kPayloadLoads<B>>();
+            wait_vmcnt_imm<(NAB == 3 ? NA + NS : 0) + NS * kPayloadLoads<B>>();
         else
             wait_vmcnt_imm<0>();
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
+    int abuf = 0;  // activation buffer of the current step
 
 #ifdef MUW_PROFILE_TILE
     uint32_t tprof[6] = {0, 0, 0, 0, 0, 0};
@@ -411,22 +417,28 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         constexpr int PAR = decltype(par)::value;
         constexpr bool STEADY = decltype(steady)::value;
         const bool full = STEADY || kp + 2 < kp_hi, more = STEADY || kp + 1 < kp_hi;
-        PanelMasks<B> mf[2], md[2];
+        PanelMasks<B> mf[NS], md[NS];
+        constexpr int AHEAD = NAB - 1;  // steps the activation DMA runs ahead
+        const int abuf_dma = abuf + AHEAD >= NAB ? abuf + AHEAD - NAB : abuf + AHEAD;
         if constexpr (STEADY) {
-            issue_a(kp + 1, PAR ^ 1);
+            issue_a(kp + AHEAD, abuf_dma);
+            const int pk = kp + 4 < kp_hi ? kp + 4 : kp + 2;  // (past the K range: any valid panel, never used)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                issue_mask_dma<B>(peek_tile(j, kp + 3), (kp + 3) % kTilePanels, lane, M_lds[wave][(kp + 3) % 3][j]);
-            // masks of the panels fetched and decoded in this step (their DMA landed before the last barrier)
-            uint32_t rf[2], rdm[2];
+            for (int j = 0; j < NS; ++j)
+                issue_mask_dma<B>(peek_tile(j, pk), pk % kTilePanels, lane, M_lds[wave][(kp + 4) % NMS][j]);
+            // masks of the panels fetched and decoded in this step (requested two and three steps ago)
+            uint32_t rf[NS], rdm[NS];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % 3][j], lane);
-                rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % 3][j], lane);
+            for (int j = 0; j < NS; ++j) {
+                rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
+                rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % NMS][j], lane);
             }
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[1]), "+v"(rdm[0]), "+v"(rdm[1]));
+            if constexpr (NS == 2)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]), "+v"(rdm[0]), "+v"(rdm[NS - 1]));
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rdm[0]));
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < NS; ++j) {
                 masks_from_lanes<B>(rf[j], mf[j]);
                 masks_from_lanes<B>(rdm[j], md[j]);
             }
@@ -434,21 +446,21 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
             open_tiles(kp + 3, false);
         } else {
             // tail (and short K ranges): scalar mask loads, waited for on the spot
-            if (more) issue_a(kp + 1, PAR ^ 1);
+            if (kp + AHEAD < kp_hi) issue_a(kp + AHEAD, abuf_dma);
             if (full) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
+                for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
                 fetch(mf, pay[PAR], ptile[PAR]);
             }
             if (kp + 3 < kp_hi) open_tiles(kp + 3, false);
             if (more) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NS; ++j)
                     if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
             }
         }
         TPROF_MARK(0);  // DMA, payload and mask loads issued
-        const uint32_t a0 = aaddr[0] + uint32_t(PAR) * ABYTES, a1 = aaddr[1] + uint32_t(PAR) * ABYTES;
+        const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
         // B fragments of this step (8 reads), first A fragments
         u32x4_t bf[4][2];
 #pragma unroll
@@ -468,10 +480,13 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         if (more) {
             // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
             // at least the activation and mask DMA and the payload loads of this step.
-            if (STEADY)
-                wait_payload<NA + 2 + 2 * kPayloadLoads<B>>(pay[PAR ^ 1]);
-            else
-                wait_payload<0>(pay[PAR ^ 1]);
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                if (STEADY)
+                    wait_payload<NA + NS + NS * kPayloadLoads<B>>(pay[PAR ^ 1][j]);
+                else
+                    wait_payload<0>(pay[PAR ^ 1][j]);
+            }
             decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
         }
         TPROF_MARK(2);  // decode (waits for the payload) and LDS writes
@@ -504,6 +519,7 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
                                                                          __builtin_bit_cast(bf16x8, bf[s][h]),
                                                                          acc[mb][s], 0, 0, 0);
         }
+        abuf = abuf + 1 == NAB ? 0 : abuf + 1;
         TPROF_MARK(3);  // MFMA loop
         end_of_step(STEADY);
         TPROF_MARK(4);  // end-of-step waits and barrier
@@ -511,25 +527,27 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
 
     if (kp_lo < kp_hi) {
         {  // (kp_lo is the first panel of a tile: splits cover whole tiles)
-            PanelMasks<B> m0[2], m1[2];
+            PanelMasks<B> m0[NS], m1[NS];
             open_tiles(kp_lo, true);
             issue_a(kp_lo, 0);
+            if (NAB == 3 && kp_lo + 1 < kp_hi) issue_a(kp_lo + 1, 1);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 0, m0[j]);
+            for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, 0, m0[j]);
             fetch(m0, pay[0], ptile[0]);
             if (kp_lo + 1 < kp_hi) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) load_panel_masks<B>(cur[j].tile, 1, m1[j]);
+                for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, 1, m1[j]);
                 fetch(m1, pay[1], ptile[1]);
             }
-            if (kp_lo + 4 < kp_hi) {  // the steady-state loop runs: masks of panels kp_lo + 1, + 2 through LDS
+            if (kp_lo + 4 < kp_hi) {  // the steady-state loop runs: masks of panels kp_lo + 1 .. + 3 through LDS
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    issue_mask_dma<B>(cur[j].tile, 1, lane, M_lds[wave][(kp_lo + 1) % 3][j]);
-                    issue_mask_dma<B>(cur[j].tile, 2, lane, M_lds[wave][(kp_lo + 2) % 3][j]);
-                }
+                for (int j = 0; j < NS; ++j)
+#pragma unroll
+                    for (int pp = 1; pp <= 3; ++pp)
+                        issue_mask_dma<B>(cur[j].tile, pp, lane, M_lds[wave][(kp_lo + pp) % NMS][j]);
             }
-            wait_payload<0>(pay[0]);
+#pragma unroll
+            for (int j = 0; j < NS; ++j) wait_payload<0>(pay[0][j]);
             decode_to_lds(m0, pay[0], ptile[0], 0);
         }
         end_of_step(false);
@@ -556,7 +574,7 @@ __global__ __launch_bounds__(256, TM == 256 ? 1 : 2) void k_pipe_gemm_bf16(PipeA
         for (int s = 0; s < 4; ++s) {
             const int64_t n = n0 + wn * 64 + s * 16 + r;
             if (n >= L.N) continue;
-            const int64_t mq = m0 + wm * (TM / 2) + mb * 16 + 4 * g;
+            const int64_t mq = m0 + wm * 64 + mb * 16 + 4 * g;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int64_t m = mq + v;
@@ -584,11 +602,9 @@ template <int B>
 muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if constexpr (B == 8 || B == 16) {
-        // 128-row tiles: two workgroups per compute unit hide each other's waits.  (The 256-row
-        // instantiation needs more than 256 registers per lane; the compiler then parks loaded payload
-        // in the accumulation registers, which forces a wait right after the loads are issued, and it
-        // measured slower.)
-        const int tm = 128;
+        // 256-row tiles with 8 waves (one workgroup per compute unit: the decode of a strip serves 256
+        // rows), 128-row tiles with 4 waves (two workgroups per compute unit) for short M
+        const int tm = t.M > 128 ? 256 : 128;
         int splits = tile_splits(L, t.M, tm);
         if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
         const int64_t kt_per = (L.KT + splits - 1) / splits;
@@ -605,7 +621,10 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
         const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
         dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
-        k_pipe_gemm_bf16<B, 128><<<grid, 256, 0, st>>>(a, L);
+        if (tm == 256)
+            k_pipe_gemm_bf16<B, 8><<<grid, 512, 0, st>>>(a, L);
+        else
+            k_pipe_gemm_bf16<B, 4><<<grid, 256, 0, st>>>(a, L);
         if (splits > 1) {
             const int64_t total = t.M * L.N;
             k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, t.M, L.N, t.Y, t.ldy,
