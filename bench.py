@@ -186,7 +186,7 @@ def bench_cfg5(args, torch, muw, synth, to_device):
             "config": {"workload": "cfg5_mlp_M2048"}, "per_gemm": res,
             "roofline": {"bound": "mfma", "achieved": total_flops_surv / total_ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": total_flops_surv / total_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                         "traffic": traffic_from_profiles("k_tile_gemm_bf16_cfg5")}}
+                         "traffic": traffic_from_profiles("k_pipe_gemm_bf16_cfg5")}}
 
 
 def _roof(bytes_algo, flops_surv, ms):
