@@ -17,6 +17,8 @@
 //     wave (the role rotates) and written to Y.  No atomics: results are bitwise reproducible.
 // Every tile issues exactly NCH 1-KiB DMA instructions (lanes past the end of the stream re-read its
 // last 16 bytes), so "tiles q and q + 1 have landed" is the static wait vmcnt((D - 1) * NCH).
+// k_stream_bf16 below serves block lengths 4 and 8; block length 16 (the memory-bound benchmark shape)
+// has its own leaner kernel in muw_stream16.hpp.
 #include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
@@ -507,6 +509,8 @@ muw_status launch_stream_b(StreamArgs a, const Layout &L, int nch, hipStream_t s
     }
 }
 
+#include "muw_stream16.hpp"
+
 }  // namespace
 
 // Can the streaming kernel take this problem?  (bf16, M <= 16, 16-byte aligned activation rows, tile
@@ -549,7 +553,7 @@ muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs
     switch (d.B) {
     case 4: rc = launch_stream_b<4>(a, L, nch, st); break;
     case 8: rc = launch_stream_b<8>(a, L, nch, st); break;
-    case 16: rc = launch_stream_b<16>(a, L, nch, st); break;
+    case 16: rc = launch_stream16(a, L, d.max_tile_bytes, st); break;
     default: return MUW_EUNSUPPORTED;
     }
     if (rc != MUW_OK) return rc;
@@ -561,5 +565,15 @@ muw_status launch_stream_gemm(const muw_desc &d, const Layout &L, const GemmArgs
     }
     return rc;
 }
+
+#ifdef MUW_PROFILE_STREAM
+extern "C" int muw_debug_stream_prof(unsigned long long *out8, int reset)
+{
+    unsigned long long z[8] = {};
+    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_stream_prof), sizeof(z)) != hipSuccess) return 1;
+    if (reset && hipMemcpyToSymbol(HIP_SYMBOL(g_stream_prof), z, sizeof(z)) != hipSuccess) return 1;
+    return 0;
+}
+#endif
 
 }  // namespace muw

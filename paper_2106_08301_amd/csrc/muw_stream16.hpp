@@ -1,0 +1,485 @@
+// muw_stream16.hpp -- the streaming kernel for block length 16 (bf16), the memory-bound benchmark
+// shape (paper Sec. 3.2: a unified block is stored as one magnitude and 16 sign bits, a pruned one as
+// nothing).  Included by muw_stream.hip inside its anonymous namespace; same walk as k_stream_bf16
+// (one persistent workgroup of 16 waves per compute unit, wave w owns tile column 16 c + w and keeps
+// its activations in registers), but written for the fewest instructions per tile: at 4 waves per
+// SIMD the kernel runs at about one instruction per SIMD every 4 cycles whatever the mix of vector
+// and scalar work, so the time per tile is the instruction count.
+//   - masks come by ONE scalar load per tile straight from the blob (the line is in L2: the DMA of
+//     that tile was issued D tiles earlier) into the mask registers the previous tile no longer
+//     needs (the loop is unrolled by two for that);
+//   - no branches in the decode: every lane decodes its record (zero for lanes without a UNIFIED
+//     block), then the DENSE lanes alone (exec = the D mask) overwrite the result with their 32 bytes;
+//   - no workgroup barrier: partial sums are handed over through R LDS slots guarded by per-wave
+//     flags (see the hand-over comment in the kernel);
+#pragma once
+
+#ifdef MUW_PROFILE_STREAM
+__device__ unsigned long long g_stream_prof[8];
+#endif
+
+// Kernel arguments.  They are read where they are used (through the scalar cache) instead of being kept
+// in scalar registers for the whole kernel: the loop needs those registers for the tile masks.  What
+// the summing wave needs sits together so that one load brings it.
+struct Stream16Out {
+    void *Y;
+    void *const *Ys;  // grouped: device array of G pointers (else null)
+    float *Ypart;     // [nchunk][G][M][N] partial sums when K is split over blockIdx.y, else null
+    int32_t ldy, M, N, ydtype, G, pad;
+};
+struct Stream16Args {
+    Stream16Out out;
+    const uint8_t *blob;
+    const void *const *blobs;
+    const uint16_t *X;
+    const void *const *Xs;
+    int32_t ldx, K, KT, NS;
+    uint32_t dir_off, streams_off;
+    int32_t nstrips, per_wg;
+};
+template <typename T>
+__device__ inline T kernarg(size_t offset)
+{
+    const __attribute__((address_space(4))) uint8_t *p =
+        (const __attribute__((address_space(4))) uint8_t *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));  // opaque: keeps the load from being hoisted out of the loop
+    return *(const __attribute__((address_space(4))) T *)(p + offset);
+}
+#define MUW_KARG(type, field) kernarg<type>(offsetof(Stream16Args, field))
+// a block of arguments (a multiple of 16 bytes) in one go
+template <typename T>
+__device__ inline T kernarg_block(size_t offset)
+{
+    static_assert(sizeof(T) % 16 == 0, "whole 16-byte units");
+    struct Raw {
+        u32x4_t v[sizeof(T) / 16];
+    } raw;
+#pragma unroll
+    for (size_t i = 0; i < sizeof(T) / 16; ++i) raw.v[i] = kernarg<u32x4_t>(offset + 16 * i);
+    return __builtin_bit_cast(T, raw);
+}
+
+struct Masks16 {
+    uint64_t u[kP], d[kP];
+};
+
+// Scalar load of a tile's masks from the blob (the address is wave-uniform; stream order: per panel
+// U then D).
+__device__ inline void load_masks16(Masks16 &m, uint64_t tile_addr)
+{
+    c_u64 *p = (c_u64 *)tile_addr;
+#pragma unroll
+    for (int i = 0; i < kP; ++i) {
+        m.u[i] = p[2 * i];
+        m.d[i] = p[2 * i + 1];
+    }
+}
+
+// A wave-uniform LDS word, read now (inline assembly: for an ordinary LDS load the compiler would also
+// wait for the DMA in flight, which it cannot tell apart from the load's target).
+__device__ inline uint32_t lds_poll(uint32_t addr)
+{
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
+// HBM -> LDS without registers: lane l's 16 bytes go to lds + 16 l.  (The 12-byte form of the
+// instruction also places lanes 16 bytes apart, so it cannot fill a gapless 768-byte tail.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wint-to-void-pointer-cast"  // (host pass: LDS pointers are 32-bit on the device)
+__device__ inline void dma_head(uint64_t lane_src, uint32_t lds)
+{
+    __builtin_amdgcn_global_load_lds((global_void_t *)lane_src, (lds_void_t *)lds, 16, 0, 0);
+}
+#pragma clang diagnostic pop
+
+// One tile of a B = 16 layer.  tile_lds: LDS address of the tile's stream; dense_lds: LDS address of
+// its DENSE blocks; m: its masks; next_addr: address in the blob of the tile decoded next, whose
+// masks go to mn; word_addr: an LDS word read along with the records (returned in word).
+__device__ inline f32x4 stream_tile16(uint32_t tile_lds, uint32_t dense_lds, const Masks16 &m,
+                                      const uint4 (&xr)[kP][2], uint64_t next_addr, Masks16 &mn,
+                                      uint32_t word_addr, uint32_t &word, uint64_t *marks)
+{
+    uint32_t rec[kP], da[kP];
+    uint32_t base_u = tile_lds + kP * 16u;  // records follow the 64 bytes of masks
+    uint32_t base_d = dense_lds;
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+        // payload order is (panel, lane): a lane's record is number (blocks of earlier panels) +
+        // (UNIFIED lanes below it) of the tile
+        rec[p] = lds_read_b32(base_u + (mbcnt64(m.u[p]) << 2));
+        da[p] = base_d + (mbcnt64(m.d[p]) << 5);
+        if (p + 1 < kP) {
+            base_u += uint32_t(__popcll(m.u[p])) << 2;
+            base_d += uint32_t(__popcll(m.d[p])) << 5;
+        }
+    }
+    asm volatile("ds_read_b32 %0, %1 offset:64" : "=v"(word) : "v"(word_addr));
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rec[0]), "+v"(rec[1]), "+v"(rec[2]), "+v"(rec[3]), "+v"(word));
+#ifdef MUW_PROFILE_STREAM
+    marks[2] = __builtin_amdgcn_s_memtime();
+#endif
+    {
+        uint64_t addr = next_addr;
+        asm volatile("" : "+s"(addr));  // (opaque: the load must not move above the wait)
+        load_masks16(mn, addr);
+    }
+    u32x4_t wlo[kP], whi[kP];
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+        // record (pack_record16): bytes {q low, signs of even elements, q high, signs of odd elements}:
+        // (rec << d) has the signs of elements 2 d and 2 d + 1 at bits 15 and 31
+        const uint32_t rc = __builtin_amdgcn_inverse_ballot_w64(m.u[p]) ? rec[p] : 0u;
+        const uint32_t qq = __builtin_amdgcn_perm(rc, rc, 0x02000200u);
+        wlo[p].x = qq | (rc & 0x80008000u);
+        wlo[p].y = qq | ((rc << 1) & 0x80008000u);
+        wlo[p].z = qq | ((rc << 2) & 0x80008000u);
+        wlo[p].w = qq | ((rc << 3) & 0x80008000u);
+        whi[p].x = qq | ((rc << 4) & 0x80008000u);
+        whi[p].y = qq | ((rc << 5) & 0x80008000u);
+        whi[p].z = qq | ((rc << 6) & 0x80008000u);
+        whi[p].w = qq | ((rc << 7) & 0x80008000u);
+        // DENSE lanes only: the stored values replace the (zero) decode.  The data arrives long after
+        // the vector instructions above have written the registers.
+        asm volatile("s_mov_b64 exec, %3\n\tds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\t"
+                     "s_mov_b64 exec, -1"
+                     : "+v"(wlo[p]), "+v"(whi[p])
+                     : "v"(da[p]), "s"(m.d[p]));
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(wlo[0]), "+v"(wlo[1]), "+v"(wlo[2]), "+v"(wlo[3]), "+v"(whi[0]), "+v"(whi[1]),
+                   "+v"(whi[2]), "+v"(whi[3]));
+#ifdef MUW_PROFILE_STREAM
+    marks[3] = __builtin_amdgcn_s_memtime();
+#endif
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][0]),
+                                                      __builtin_bit_cast(bf16x8, wlo[p]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xr[p][1]),
+                                                      __builtin_bit_cast(bf16x8, whi[p]), acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// SLOT256: bytes of a ring slot in units of 256 (>= the largest tile stream; 1 KiB plus what one more
+// DMA instruction of 4, 12 or 16 bytes per lane brings).  D: tiles the DMA runs ahead.  R: strips
+// whose partial sums can be in LDS at once.  LAG: a strip is summed LAG iterations after its delivery.
+template <int SLOT256, int D, int R, int LAG>
+__global__ __launch_bounds__(kWaves * 64) void k_stream16_bf16(Stream16Args)
+{
+    constexpr int SLOT = SLOT256 * 256;
+    constexpr int NSLOT = D + 1;
+    constexpr int TAIL = SLOT - 1024;  // bytes of the second DMA instruction
+    static_assert(TAIL == 0 || TAIL == 256 || TAIL == 768 || TAIL == 1024, "slot = 1 KiB + one DMA instruction");
+    static_assert(LAG >= 1 && LAG < R, "a slot is reused R strips later");
+    static_assert(D >= 2, "the mask load takes the address the DMA looked up an iteration earlier");
+    constexpr int NCH = TAIL ? 2 : 1;
+    __shared__ __attribute__((aligned(16))) uint8_t ring[kWaves][NSLOT * SLOT];
+    __shared__ __attribute__((aligned(16))) float red[R][kWaves][64][4];
+    // hand-over words of the R partial-sum slots: [s][w] generation wave w has delivered to slot s,
+    // [s][16 + i] (16 copies) generation that has been summed in slot s
+    __shared__ uint32_t sync[R][32];
+    if (threadIdx.x < R * 32) sync[threadIdx.x / 32][threadIdx.x % 32] = 0;
+    __syncthreads();
+
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63, r = lane & 15, g4 = lane >> 4;
+    const int chunk = blockIdx.y;
+    const int kt = chunk * kWaves + wave;
+    const int KT = MUW_KARG(int32_t, KT), NS = MUW_KARG(int32_t, NS);
+    const bool active = kt < KT;
+
+    const int s_lo = blockIdx.x * MUW_KARG(int32_t, per_wg);
+    int s_hi = s_lo + MUW_KARG(int32_t, per_wg);
+    if (s_hi > MUW_KARG(int32_t, nstrips)) s_hi = MUW_KARG(int32_t, nstrips);
+    if (s_lo >= s_hi) return;
+    const int nseq = s_hi - s_lo;  // this workgroup's strips, over all matrices: element q = strip s_lo + q
+
+    // ---- hand-over of the partial sums.  Strip q uses slot q % R in generation q / R + 1.  A wave stores
+    //      its partial 16x16 sums there and then its flag (LDS executes a wave's operations in order).
+    //      Strip s is summed by wave s % 16 during its iteration s + LAG (after the loop for the last
+    //      strips), in wave order (bitwise reproducible), once all 16 flags show the generation; it then
+    //      marks the slot summed.  Before storing, a wave checks that the previous generation of the
+    //      slot has been summed.  Both waits sleep and poll; they end because the wave at the lowest
+    //      iteration never waits: what it needs was delivered, and summed, in earlier iterations of
+    //      waves that are at least as far.
+    const uint32_t sync_wave = lds_offset(&sync[0][wave]);         // + 128 slot: this wave's flag; + 64: summed
+    const uint32_t sync_lane = lds_offset(&sync[0][lane & 15]);    // + 128 slot: flag of wave lane % 16
+    const uint32_t red_lane = lds_offset(red[0][wave][lane]);      // + 16384 slot: this lane's partial sums
+    const uint32_t red_sum = lds_offset(red[0][0][lane]);          // + 16384 slot + 1024 wave
+
+    auto sum_strip = [&](int qs) {
+        const uint32_t slot = uint32_t(qs) % R, gen = uint32_t(qs) / R + 1;
+        const uint32_t fa = sync_lane + slot * 128u;
+        while (true) {
+            const uint32_t f = lds_poll(fa);
+            if (__builtin_amdgcn_ballot_w64(f < gen) == 0) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        f32x4 t = {0.f, 0.f, 0.f, 0.f};  // waves without a tile column delivered zeros
+        const uint32_t ra = red_sum + slot * 16384u;
+        // (literal offsets: addresses computed in registers would be hoisted out of the tile loop and
+        // crowd its registers)
+#define MUW_SUM8(O0, O1, O2, O3, O4, O5, O6, O7)                                                               \
+    {                                                                                                          \
+        f32x4 p0, p1, p2, p3, p4, p5, p6, p7;                                                                  \
+        asm volatile("ds_read_b128 %0, %8 offset:" #O0 "\n\tds_read_b128 %1, %8 offset:" #O1                   \
+                     "\n\tds_read_b128 %2, %8 offset:" #O2 "\n\tds_read_b128 %3, %8 offset:" #O3              \
+                     "\n\tds_read_b128 %4, %8 offset:" #O4 "\n\tds_read_b128 %5, %8 offset:" #O5              \
+                     "\n\tds_read_b128 %6, %8 offset:" #O6 "\n\tds_read_b128 %7, %8 offset:" #O7              \
+                     "\n\ts_waitcnt lgkmcnt(0)"                                                                \
+                     : "=&v"(p0), "=&v"(p1), "=&v"(p2), "=&v"(p3), "=&v"(p4), "=&v"(p5), "=&v"(p6), "=&v"(p7)  \
+                     : "v"(ra));                                                                               \
+        t += p0;                                                                                               \
+        t += p1;                                                                                               \
+        t += p2;                                                                                               \
+        t += p3;                                                                                               \
+        t += p4;                                                                                               \
+        t += p5;                                                                                               \
+        t += p6;                                                                                               \
+        t += p7;                                                                                               \
+    }
+        MUW_SUM8(0, 1024, 2048, 3072, 4096, 5120, 6144, 7168)
+        MUW_SUM8(8192, 9216, 10240, 11264, 12288, 13312, 14336, 15360)
+#undef MUW_SUM8
+        asm volatile("ds_write_b32 %0, %1 offset:64" ::"v"(fa), "v"(gen) : "memory");  // the slot is free again
+        const Stream16Out o = kernarg_block<Stream16Out>(offsetof(Stream16Args, out));
+        const int gs = s_lo + qs, gi_s = gs / NS, strip_s = gs % NS;
+        const int n = strip_s * kStripRows + r;
+        const uint64_t Y = o.Ys ? table_entry(o.Ys, gi_s) : reinterpret_cast<uint64_t>(o.Y);
+        if (n < o.N) {
+            const uint64_t Yp = reinterpret_cast<uint64_t>(o.Ypart) +
+                                uint64_t(int64_t(chunk) * o.G + gi_s) * uint64_t(o.M) * uint64_t(o.N) * 4u;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = 4 * g4 + v;
+                if (m >= o.M) continue;
+                if (o.Ypart)
+                    *(g_float *)(Yp + uint64_t(uint32_t(m * o.N + n) * 4u)) = t[v];
+                else if (o.ydtype == MUW_F32)
+                    *(g_float *)(Y + uint64_t(uint32_t(m * o.ldy + n) * 4u)) = t[v];
+                else
+                    *(g_u16 *)(Y + uint64_t(uint32_t(m * o.ldy + n) * 2u)) = f32_to_bf16_rne(t[v]);
+            }
+        }
+    };
+    // deliver the partial sums of strip q; `summed` is a look at this slot's summed word taken earlier
+    int turn = wave + LAG;  // iterations until this wave sums a strip
+    auto deliver = [&](int q, f32x4 acc, uint32_t summed_v) {
+        const uint32_t slot = uint32_t(q) % R, gen = uint32_t(q) / R + 1;
+        uint32_t summed = uint32_t(__builtin_amdgcn_readfirstlane(summed_v));
+        while (summed + 1 < gen) {
+            __builtin_amdgcn_s_sleep(2);
+            summed = uint32_t(__builtin_amdgcn_readfirstlane(lds_poll(sync_wave + slot * 128u + 64u)));
+        }
+        asm volatile("ds_write_b128 %0, %1" ::"v"(red_lane + slot * 16384u), "v"(acc) : "memory");
+        asm volatile("ds_write_b32 %0, %1" ::"v"(sync_wave + slot * 128u), "v"(gen) : "memory");
+        if (turn == 0) {
+            sum_strip(q - LAG);
+            turn = kWaves;
+        }
+        --turn;
+    };
+
+    if (!active) {
+        // no tile column (K is not a multiple of 4096): deliver zeros, take the turns at summing
+        for (int q = 0; q < nseq; ++q) {
+            const uint32_t sv = lds_poll(sync_wave + (uint32_t(q) % R) * 128u + 64u);
+            deliver(q, f32x4{0.f, 0.f, 0.f, 0.f}, sv);
+        }
+    } else {
+        // ---- directory window: lane l holds the stream address and the offset of the DENSE blocks
+        //      of sequence element qbase + l
+        uint64_t q_addr = 0;
+        uint32_t q_doff = 0, q_last = 0;
+        auto refill = [&](int base) {
+            const int qq = base + lane;
+            const int gs = s_lo + qq;
+            const int gi = gs / NS;
+            const int64_t strip = gs % NS;
+            const bool ok = qq < nseq;
+            uint64_t blob = reinterpret_cast<uint64_t>(MUW_KARG(const uint8_t *, blob));
+            const void *const *blobs = MUW_KARG(const void *const *, blobs);
+            if (blobs) blob = ((const __attribute__((address_space(1))) uint64_t *)blobs)[ok ? gi : 0];
+            q_addr = blob;  // a readable address for elements past the end (never fetched, masks unused)
+            q_doff = 0;
+            q_last = 0;
+            if (ok) {
+                g_cu32 *de = (g_cu32 *)(blob + MUW_KARG(uint32_t, dir_off) + uint64_t(strip * KT + kt) * sizeof(DirEntry));
+                const uint32_t off16 = de[0], cnt = de[1], next = de[2];
+                q_last = (next - off16) * 16u - 16u;  // offset of the stream's last 16 bytes
+                q_addr = blob + MUW_KARG(uint32_t, streams_off) + uint64_t(off16) * 16;
+                q_doff = kP * 16u + (((cnt & 0xffffu) * 4u + 15u) & ~15u);  // masks | records | DENSE blocks
+            }
+            // Drain on every path: a load left pending here would turn each later read of the window
+            // registers into a wait for all DMA prefetches as well.
+            wait_vmcnt<0>();
+        };
+        auto window_addr = [&](int l) {
+            const uint32_t lo = __builtin_amdgcn_readlane(uint32_t(q_addr), l);
+            const uint32_t hi = __builtin_amdgcn_readlane(uint32_t(q_addr >> 32), l);
+            return (uint64_t(hi) << 32) | lo;
+        };
+        const uint32_t ring_lds = uint32_t(__builtin_amdgcn_readfirstlane(lds_offset(ring[wave])));
+        const uint32_t off0 = uint32_t(lane) * 16u;
+        // blob addresses of the tiles q + 1 .. q + D: the DMA of tile q + D looks its address up (last
+        // entry), the mask load of tile q + 1 uses it again D - 1 iterations later (first entry)
+        uint64_t next_tile[D];
+        // ---- fetch a tile: 1 KiB and (if a slot is longer) one more instruction for the rest of the slot.
+        //      Lanes past the end of the stream fetch its last 16 bytes again: every tile issues the same
+        //      number of DMA instructions (the vmcnt waits count them) and HBM traffic stays the stream's.
+        auto issue = [&](int l, uint32_t slot_off) {
+            const uint64_t base = window_addr(l);
+            next_tile[D - 1] = base;
+            const uint32_t last = __builtin_amdgcn_readlane(q_last, l);
+            dma_head(base + (off0 < last ? off0 : last), ring_lds + slot_off);
+            if constexpr (TAIL != 0) {
+                const uint32_t o1 = off0 + 1024u < last ? off0 + 1024u : last;
+                if (TAIL == 1024 || lane < TAIL / 16) dma_head(base + o1, ring_lds + slot_off + 1024u);
+            }
+        };
+
+        uint4 xr[kP][2];
+        auto load_x = [&](int gi) {
+            const void *const *Xs = MUW_KARG(const void *const *, Xs);
+            const uint64_t X = Xs ? table_entry(Xs, gi) : reinterpret_cast<uint64_t>(MUW_KARG(const uint16_t *, X));
+            const int ldx = MUW_KARG(int32_t, ldx), M = MUW_KARG(int32_t, out.M), K = MUW_KARG(int32_t, K);
+#pragma unroll
+            for (int p = 0; p < kP; ++p)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int k = kt * kTileK + p * kPanelK + 16 * g4 + 8 * h;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (r < M && k + 8 <= K) {
+                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
+                        v = make_uint4(t.x, t.y, t.z, t.w);
+                    }
+                    xr[p][h] = v;
+                }
+            // Drain here, once per matrix, so that no later use of xr needs a wait that would also
+            // wait for the DMA prefetches in flight.
+            wait_vmcnt<0>();
+        };
+
+        int gi = s_lo / NS, left = NS - s_lo % NS;  // matrix of element q; its strips still to do
+        refill(0);
+        for (int qi = 0; qi < D && qi < nseq; ++qi) issue(qi, uint32_t(qi) * SLOT);
+#pragma unroll
+        for (int i = 0; i < D; ++i) next_tile[i] = window_addr(i + 1 < 63 ? i + 1 : 63);  // (past the end: a readable address)
+        load_x(gi);
+        Masks16 mA, mB;
+        load_masks16(mA, window_addr(0));
+
+        int q = 0, wl = 0;                      // element, and its lane in the window
+        int next_refill = 64 - D;               // element at which the window runs out
+        uint32_t cur = 0, prv = uint32_t(D) * SLOT;  // ring offsets of element q and of element q + D (= q - 1)
+#ifdef MUW_PROFILE_STREAM
+        uint32_t pacc[5] = {0, 0, 0, 0, 0};
+#endif
+        auto step = [&](const Masks16 &m, Masks16 &mn) {
+            uint64_t marks[6] = {};
+#ifdef MUW_PROFILE_STREAM
+            marks[0] = __builtin_amdgcn_s_memtime();
+#endif
+            if (left == 0) {
+                ++gi;
+                left = NS;
+                load_x(gi);
+            }
+            --left;
+            const uint64_t mask_addr = next_tile[0];  // tile q + 1
+            if (q + D < nseq) {
+                if (q == next_refill) {
+                    refill(q);
+                    wl = 0;
+                    next_refill = q + 64 - D;
+                }
+                issue(wl + D, prv);
+                wait_vmcnt<D * NCH>();  // tile q has landed
+            } else {
+                wait_vmcnt<0>();
+            }
+#ifdef MUW_PROFILE_STREAM
+            marks[1] = __builtin_amdgcn_s_memtime();
+#endif
+            const uint32_t tl = ring_lds + cur;
+            const uint32_t doff = __builtin_amdgcn_readlane(q_doff, wl);
+            uint32_t sv;
+            const f32x4 acc = stream_tile16(tl, tl + doff, m, xr, mask_addr, mn,
+                                            sync_wave + (uint32_t(q) % R) * 128u, sv, marks);
+#ifdef MUW_PROFILE_STREAM
+            {
+                f32x4 a2 = acc;
+                asm volatile("" : "+v"(a2));
+                const uint32_t slot = uint32_t(q) % R;
+                asm volatile("ds_write_b128 %0, %1" ::"v"(red_lane + slot * 16384u), "v"(a2) : "memory");  // (same data twice)
+                marks[4] = __builtin_amdgcn_s_memtime();
+            }
+#endif
+            deliver(q, acc, sv);
+#ifdef MUW_PROFILE_STREAM
+            marks[5] = __builtin_amdgcn_s_memtime();
+#pragma unroll
+            for (int i = 0; i < 5; ++i) pacc[i] += uint32_t(marks[i + 1] - marks[i]);
+#endif
+#pragma unroll
+            for (int i = 0; i + 1 < D; ++i) next_tile[i] = next_tile[i + 1];
+            prv = cur;
+            cur = cur + SLOT == NSLOT * SLOT ? 0 : cur + SLOT;
+            ++wl;
+            ++q;
+        };
+        while (true) {
+            step(mA, mB);
+            if (q == nseq) break;
+            step(mB, mA);
+            if (q == nseq) break;
+        }
+#ifdef MUW_PROFILE_STREAM
+        if (lane == 0)
+            for (int i = 0; i < 5; ++i) atomicAdd(&g_stream_prof[i], (unsigned long long)pacc[i]);
+#endif
+    }
+    // the last strips
+    for (int qs = nseq - LAG < 0 ? 0 : nseq - LAG; qs < nseq; ++qs)
+        if (wave == (qs & (kWaves - 1))) sum_strip(qs);
+}
+
+template <int SLOT256, int D, int R, int LAG>
+muw_status launch_stream16_variant(StreamArgs a, const Layout &L, hipStream_t st)
+{
+    Stream16Args k{};
+    k.out = Stream16Out{a.Y, a.Ys, a.Ypart, a.ldy, a.M, int32_t(L.N), a.ydtype, a.G, 0};
+    k.blob = a.blob;
+    k.blobs = a.blobs;
+    k.X = a.X;
+    k.Xs = a.Xs;
+    k.ldx = a.ldx;
+    k.K = int32_t(L.K);
+    k.KT = int32_t(L.KT);
+    k.NS = int32_t(L.NS);
+    k.dir_off = uint32_t(L.dir_off);
+    k.streams_off = uint32_t(L.streams_off);
+    const int cus = device_cus();
+    k.nstrips = int32_t(L.NS) * a.G;
+    int grid = k.nstrips < cus ? k.nstrips : cus;
+    k.per_wg = (k.nstrips + grid - 1) / grid;
+    grid = (k.nstrips + k.per_wg - 1) / k.per_wg;
+    dim3 g(unsigned(grid), unsigned(a.nchunk), 1);
+    k_stream16_bf16<SLOT256, D, R, LAG><<<g, kWaves * 64, 0, st>>>(k);
+    return hip_status(hipGetLastError());
+}
+
+// 16 per-wave rings of (D + 1) slots plus R x 16 KiB of partial sums fit the 160 KiB of LDS.
+inline muw_status launch_stream16(StreamArgs a, const Layout &L, int tile_bytes, hipStream_t st)
+{
+    const int slot256 = (tile_bytes + 255) / 256;
+    if (slot256 <= 4) return launch_stream16_variant<4, 4, 4, 2>(a, L, st);
+    if (slot256 <= 5) return launch_stream16_variant<5, 3, 4, 2>(a, L, st);
+    if (slot256 <= 7) return launch_stream16_variant<7, 2, 4, 2>(a, L, st);
+    if (slot256 <= 8) return launch_stream16_variant<8, 2, 3, 1>(a, L, st);
+    return MUW_EUNSUPPORTED;
+}
