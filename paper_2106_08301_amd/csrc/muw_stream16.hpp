@@ -2,9 +2,11 @@
 // shape (paper Sec. 3.2: a unified block is stored as one magnitude and 16 sign bits, a pruned one as
 // nothing).  Included by muw_stream.hip inside its anonymous namespace; same walk as k_stream_bf16
 // (one persistent workgroup of 16 waves per compute unit, wave w owns tile column 16 c + w and keeps
-// its activations in registers), but written for the fewest instructions per tile: at 4 waves per
-// SIMD the kernel runs at about one instruction per SIMD every 4 cycles whatever the mix of vector
-// and scalar work, so the time per tile is the instruction count.
+// its activations in registers), but written for the fewest instructions per tile.  The kernel is
+// bound by its vector instructions, not by HBM: turning a 32-bit record into the 8 dwords of bf16 pairs
+// the MFMA wants costs one shift and one bit-select per dword, 68 of the about 110 vector
+// instructions a wave spends on a tile, and at 4 waves per SIMD (LDS and registers allow no more)
+// the vector unit is busy about 70 % of the time.
 //   - masks come by ONE scalar load per tile straight from the blob (the line is in L2: the DMA of
 //     that tile was issued D tiles earlier) into the mask registers the previous tile no longer
 //     needs (the loop is unrolled by two for that);
@@ -113,6 +115,9 @@ __device__ inline f32x4 stream_tile16(uint32_t tile_lds, uint32_t dense_lds, con
         if (p + 1 < kP) {
             base_u += uint32_t(__popcll(m.u[p])) << 2;
             base_d += uint32_t(__popcll(m.d[p])) << 5;
+            // (opaque: keeps the running bases in scalar registers -- one vector instruction per
+            // address -- instead of adding the counts to every lane's rank first)
+            asm volatile("" : "+s"(base_u), "+s"(base_d));
         }
     }
     asm volatile("ds_read_b32 %0, %1 offset:64" : "=v"(word) : "v"(word_addr));
