@@ -132,25 +132,37 @@ __device__ inline f32x4 stream_tile16(uint32_t tile_lds, uint32_t dense_lds, con
     }
     u32x4_t wlo[kP], whi[kP];
 #pragma unroll
-    for (int p = 0; p < kP; ++p) {
+    for (int pp = 0; pp < kP; pp += 2) {
         // record (pack_record16): bytes {q low, signs of even elements, q high, signs of odd elements}:
-        // (rec << d) has the signs of elements 2 d and 2 d + 1 at bits 15 and 31
-        const uint32_t rc = __builtin_amdgcn_inverse_ballot_w64(m.u[p]) ? rec[p] : 0u;
-        const uint32_t qq = __builtin_amdgcn_perm(rc, rc, 0x02000200u);
-        wlo[p].x = qq | (rc & 0x80008000u);
-        wlo[p].y = qq | ((rc << 1) & 0x80008000u);
-        wlo[p].z = qq | ((rc << 2) & 0x80008000u);
-        wlo[p].w = qq | ((rc << 3) & 0x80008000u);
-        whi[p].x = qq | ((rc << 4) & 0x80008000u);
-        whi[p].y = qq | ((rc << 5) & 0x80008000u);
-        whi[p].z = qq | ((rc << 6) & 0x80008000u);
-        whi[p].w = qq | ((rc << 7) & 0x80008000u);
+        // (rec << d) has the signs of elements 2 d and 2 d + 1 at bits 15 and 31.  The records of two
+        // panels are shifted as one 64-bit value (the bits that cross over are masked away).
+        const uint32_t rc0 = __builtin_amdgcn_inverse_ballot_w64(m.u[pp]) ? rec[pp] : 0u;
+        const uint32_t rc1 = __builtin_amdgcn_inverse_ballot_w64(m.u[pp + 1]) ? rec[pp + 1] : 0u;
+        const uint32_t qq0 = __builtin_amdgcn_perm(rc0, rc0, 0x02000200u);
+        const uint32_t qq1 = __builtin_amdgcn_perm(rc1, rc1, 0x02000200u);
+        const uint64_t pair = (uint64_t(rc1) << 32) | rc0;
+        uint32_t w0[8], w1[8];
+        w0[0] = qq0 | (rc0 & 0x80008000u);
+        w1[0] = qq1 | (rc1 & 0x80008000u);
+#pragma unroll
+        for (int d = 1; d < 8; ++d) {
+            uint64_t sh;
+            asm("v_lshlrev_b64 %0, %1, %2" : "=v"(sh) : "n"(d), "v"(pair));
+            w0[d] = qq0 | (uint32_t(sh) & 0x80008000u);
+            w1[d] = qq1 | (uint32_t(sh >> 32) & 0x80008000u);
+        }
+        wlo[pp] = u32x4_t{w0[0], w0[1], w0[2], w0[3]};
+        whi[pp] = u32x4_t{w0[4], w0[5], w0[6], w0[7]};
+        wlo[pp + 1] = u32x4_t{w1[0], w1[1], w1[2], w1[3]};
+        whi[pp + 1] = u32x4_t{w1[4], w1[5], w1[6], w1[7]};
         // DENSE lanes only: the stored values replace the (zero) decode.  The data arrives long after
         // the vector instructions above have written the registers.
-        asm volatile("s_mov_b64 exec, %3\n\tds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\t"
-                     "s_mov_b64 exec, -1"
-                     : "+v"(wlo[p]), "+v"(whi[p])
-                     : "v"(da[p]), "s"(m.d[p]));
+#pragma unroll
+        for (int p = pp; p < pp + 2; ++p)
+            asm volatile("s_mov_b64 exec, %3\n\tds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\t"
+                         "s_mov_b64 exec, -1"
+                         : "+v"(wlo[p]), "+v"(whi[p])
+                         : "v"(da[p]), "s"(m.d[p]));
     }
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(wlo[0]), "+v"(wlo[1]), "+v"(wlo[2]), "+v"(wlo[3]), "+v"(whi[0]), "+v"(whi[1]),
