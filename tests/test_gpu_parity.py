@@ -188,6 +188,43 @@ def test_gemm_grouped_matches_oracle(muw, oracle, M):
         check_close(to_f64(Y), ref)
 
 
+STREAM16_CASES = [
+    # M, N, K, r_u, r_p, (lowest, highest) largest tile stream in bytes: the small-M kernel for block
+    # length 16 sizes its LDS ring slots (1, 1.25, 1.75, 2 KiB) by the largest tile stream of the layer
+    (3, 40, 512, 0.5, 0.5, (1, 1024)),
+    (16, 72, 768, 1.0, 0.0, (1025, 1280)),      # every block unified: 64 + 256 * 4 bytes
+    (7, 64, 1024, 0.7, 0.25, (1281, 1792)),     # the benchmark mix
+    (9, 96, 1024, 0.0, 0.82, (1793, 2048)),     # a fifth of the blocks dense
+    (5, 40, 8192, 0.7, 0.25, (1281, 1792)),     # K beyond one 4096-wide chunk: partial outputs, second kernel
+    (16, 24, 4352, 0.6, 0.3, (1, 2048)),        # 4096 + one ragged tile column
+]
+
+
+@pytest.mark.parametrize("M,N,K,r_u,r_p,span", STREAM16_CASES)
+def test_small_m_kernel_for_block_length_16(muw, oracle, M, N, K, r_u, r_p, span):
+    case = synth.LinearCase("t", M, N, K, 16, r_u, r_p, "bf16", 0.02, 700 + M + N)
+    X, W = synth.make_linear(case)
+    (_, _, _, What), _ = oracle_encode(oracle, W, 16, r_u, r_p)
+    layer = muw.muw_encode(to_device(W), 16, r_u, r_p)
+    assert span[0] <= layer.desc.max_tile_bytes <= span[1], layer.desc.max_tile_bytes
+    check_close(to_f64(muw.muw_gemm(layer, to_device(X))), oracle.gemm(X.f64(), What))
+
+
+def test_small_m_kernel_long_walk_over_several_matrices(muw, oracle):
+    # 24 matrices x 688 strips = 16512 strips: each of the 256 workgroups walks 64 or 65 strips, across
+    # matrix boundaries and past the 64 entries its directory window holds at a time
+    G, M, N, K, B = 24, 4, 11008, 256, 16
+    case = synth.LinearCase("t", M, N, K, B, 0.7, 0.25, "bf16", 0.02, 811)
+    _, W = synth.make_linear(case)
+    (_, _, _, What), _ = oracle_encode(oracle, W, B, 0.7, 0.25)
+    base = muw.muw_encode(to_device(W), B, 0.7, 0.25)
+    layers = [muw.EncodedLayer(base.desc, base.blob.clone()) for _ in range(G)]
+    Xg = [synth.normal_tensor(900 + g, (M, K), 1.0, "bf16", stream=3) for g in range(G)]
+    Ys = muw.muw_gemm_grouped(muw.GemmGroup(layers, [to_device(x) for x in Xg]))
+    for g in (0, 1, 11, 22, 23):
+        check_close(to_f64(Ys[g]), oracle.gemm(Xg[g].f64(), What))
+
+
 CONV_CASES = [
     # Nb, Cin, H, W, Cout, ks, stride, pad, B, dtype
     (2, 16, 9, 10, 20, 3, 1, 1, 4, "bf16"),
