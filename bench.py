@@ -226,9 +226,9 @@ def report_all(args, torch, muw, synth, to_device):
         Xd = to_device(Xs).repeat(case.batch // min(distinct, case.batch), 1, 1, 1).contiguous()
         layer = muw.muw_encode(Wd, case.B, case.r_unify, case.r_prune)
         Y = torch.empty((case.batch, case.Cout, case.OH, case.OW), dtype=torch.float32, device="cuda")
-        _, ms = time_steps(torch, lambda: muw.muw_conv2d(layer, Xd, case.stride, case.pad, out=Y), 5, 2)
+        _, ms = time_steps(torch, lambda: muw.muw_conv2d(layer, Xd, case.stride, case.pad, out=Y), 30, 10)
         _, ms_torch = time_steps(torch, lambda: torch.nn.functional.conv2d(Xd, Wd, stride=case.stride,
-                                                                           padding=case.pad), 5, 2)
+                                                                           padding=case.pad), 30, 10)
         b = layer.compressed_bytes + Xd.numel() * 2 + Y.numel() * 4
         surv = 2.0 * case.M * case.B * (layer.NB - layer.desc.n_pruned)
         return {"config": name, "ms": ms, "algorithmic_GBps": b / ms / 1e6,

@@ -15,6 +15,7 @@
 // not fill the chip splits K into fp32 partial sums added in split order, so results are bitwise
 // reproducible.  Two workgroups per compute unit hide each other's load/decode phase.  Linear layers with
 // B = 8, 16 and K a multiple of 64 take the software-pipelined kernel of muw_mfma_pipe.hpp instead.
+#include <algorithm>
 #include <type_traits>
 
 #include "muw_decode.hpp"
@@ -40,6 +41,8 @@ struct TileGemmArgs {
     // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per); partial sums go to Ypart[z][M][N] (fp32)
     int32_t kp_per;
     float *Ypart;
+    // 1x1 convolution run as a linear layer on gathered pixels: Y is NCHW [M / pix][N][pix] (0: Y[M][ldy])
+    int64_t pix;
 };
 
 // Index (in 16-byte units) of chunk `chunk` of LDS row `row`.  Rows are 128 bytes (32 banks), so rows of
@@ -48,22 +51,27 @@ struct TileGemmArgs {
 __device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }
 
 // NCHW -> NHWC copy of a bf16 tensor (64 channels x 64 pixels per workgroup through LDS), so that the
-// implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.
+// implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.  With
+// step > 1 only every step-th pixel of every step-th row is taken (OH x OW of them): the input of a
+// strided 1x1 convolution, which then is a plain GEMM over the gathered pixels.
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                      int C, int P)
+                                                      int C, int H, int W, int OH, int OW, int step)
 {
     __shared__ uint16_t t[64][66];
     const int64_t b = blockIdx.z;
+    const int P = OH * OW;
     const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int p = p0 + tx;
+    const int64_t sp = step == 1 ? p : int64_t(p / OW) * step * W + int64_t(p % OW) * step;  // source pixel
     for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i, p = p0 + tx;
-        t[i][tx] = (c < C && p < P) ? src[(b * C + c) * P + p] : uint16_t(0);
+        const int c = c0 + i;
+        t[i][tx] = (c < C && p < P) ? src[(b * C + c) * (int64_t(H) * W) + sp] : uint16_t(0);
     }
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {
-        const int p = p0 + i, c = c0 + tx;
-        if (p < P && c < C) dst[(b * P + p) * C + c] = t[tx][i];
+        const int q = p0 + i, c = c0 + tx;
+        if (q < P && c < C) dst[(b * P + q) * C + c] = t[tx][i];
     }
 }
 
@@ -255,14 +263,17 @@ int tile_cus()
     return cus;
 }
 
-// How many K splits make the launch fill the chip (two workgroups per compute unit), given that a
-// split must cover whole tiles and that the partial sums need M*N*4 bytes each.
-int tile_splits(const Layout &L, int64_t M, int64_t tm = 128)
+// How many K splits a launch is cut into.  Splitting costs a round trip of fp32 partial sums (M*N*4
+// bytes per split, written and read again by the reduction), so it is worth it only when the plain
+// launch leaves most of the chip idle: below half of the resident workgroups for the kernel without
+// prefetch (which also needs the extra workgroups to hide its load latency), below a quarter for the
+// pipelined one (measured on the ResNet-50 layer shapes).  A split covers whole tiles.
+int tile_splits(const Layout &L, int64_t M, int64_t tm = 128, bool pipelined = false)
 {
     const int64_t wgs = ((L.N + kTN - 1) / kTN) * ((M + tm - 1) / tm);
-    const int64_t want = 2 * int64_t(tile_cus());
-    if (wgs >= want || L.KT < 2) return 1;
-    int64_t s = (want + wgs - 1) / wgs;
+    const int64_t resident = int64_t(tile_cus()) * (tm >= 256 ? 1 : 2);
+    if (wgs > resident / (pipelined ? 4 : 2) || L.KT < 2) return 1;
+    int64_t s = (resident + wgs - 1) / wgs;
     if (s > L.KT) s = L.KT;
     if (s > 16) s = 16;
     return int(s);
@@ -310,7 +321,8 @@ bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 
 size_t tile_gemm_workspace_bytes(const Layout &L, int64_t M)
 {
-    const int s = tile_splits(L, M);
+    // (whichever kernel takes the problem: the larger of the two split counts)
+    const int s = std::max(tile_splits(L, M), tile_splits(L, M, M > 128 ? 256 : 128, true));
     return s > 1 ? size_t(s) * size_t(M) * size_t(L.N) * 4u : 0;
 }
 
@@ -343,6 +355,9 @@ bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
     return true;
 }
 
+// 1x1, no padding (any stride): every output pixel reads exactly one input pixel
+bool conv_is_pointwise(const muw_desc &d, const ConvArgs &a) { return d.KH == 1 && d.KW == 1 && a.pad == 0; }
+
 size_t tile_conv_nhwc_bytes(const muw_desc &d, const ConvArgs &a)
 {
     return size_t(align16(uint64_t(a.Nb) * uint64_t(a.H) * uint64_t(a.W) * uint64_t(d.Cin) * 2u));
@@ -359,9 +374,35 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     const size_t nhwc = tile_conv_nhwc_bytes(d, c);
     void *part = static_cast<uint8_t *>(ws) + nhwc;
     const size_t part_bytes = ws_bytes - nhwc;
+    if (conv_is_pointwise(d, c)) {
+        // a 1x1 convolution without padding is a linear layer over the (sampled) pixels
+        const int P = int(c.OH * c.OW);
+        dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
+        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin,
+                                          int(c.H), int(c.W), int(c.OH), int(c.OW), c.stride);
+        TileGemmArgs a{};
+        a.blob = static_cast<const uint8_t *>(c.blob);
+        a.X = static_cast<const uint16_t *>(ws);
+        a.Y = c.Y;
+        a.M = c.Nb * c.OH * c.OW;
+        a.ldx = d.Cin;
+        a.ldy = L.N;
+        a.ydtype = c.ydtype;
+        a.pix = P;
+        switch (d.B) {
+        case 8:
+            if (pipe_applicable<8>(a, L)) return launch_pipe<8>(a, L, part, part_bytes, st);
+            break;
+        case 16:
+            if (pipe_applicable<16>(a, L)) return launch_pipe<16>(a, L, part, part_bytes, st);
+            break;
+        default: break;
+        }
+    }
     const int P = int(c.H * c.W);
     dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
-    k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin, P);
+    k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin,
+                                      int(c.H), int(c.W), int(c.H), int(c.W), 1);
     TileGemmArgs a{};
     a.blob = static_cast<const uint8_t *>(c.blob);
     a.X = static_cast<const uint16_t *>(ws);

@@ -253,6 +253,7 @@ struct PipeArgs {
     int32_t M, ydtype;
     int64_t ldx, ldy;
     int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
+    int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a 1x1 convolution's output)
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
 };
 
@@ -575,6 +576,26 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             const int64_t n = n0 + wn * 64 + s * 16 + r;
             if (n >= L.N) continue;
             const int64_t mq = m0 + wm * 64 + mb * 16 + 4 * g;
+            if (a.pix && !a.Ypart) {
+                // NCHW: for a fixed output channel the lane's 4 rows are 4 consecutive pixels
+                const int64_t pix = a.pix;
+                if ((pix & 3) == 0 && mq + 3 < a.M && a.ydtype == MUW_F32) {
+                    const int64_t b = mq / pix, pp = mq % pix;
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(a.Y) + (b * L.N + n) * pix + pp) = acc[mb][s];
+                    continue;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t m = mq + v;
+                    if (m >= a.M) continue;
+                    const int64_t idx = ((m / pix) * L.N + n) * pix + m % pix;
+                    if (a.ydtype == MUW_F32)
+                        static_cast<float *>(a.Y)[idx] = acc[mb][s][v];
+                    else
+                        static_cast<uint16_t *>(a.Y)[idx] = f32_to_bf16_rne(acc[mb][s][v]);
+                }
+                continue;
+            }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int64_t m = mq + v;
@@ -605,7 +626,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         // 256-row tiles with 8 waves (one workgroup per compute unit: the decode of a strip serves 256
         // rows), 128-row tiles with 4 waves (two workgroups per compute unit) for short M
         const int tm = t.M > 128 ? 256 : 128;
-        int splits = tile_splits(L, t.M, tm);
+        int splits = tile_splits(L, t.M, tm, true);
         if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
         const int64_t kt_per = (L.KT + splits - 1) / splits;
         splits = int((L.KT + kt_per - 1) / kt_per);
@@ -618,6 +639,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.ldx = t.ldx;
         a.ldy = t.ldy;
         a.kp_per = int32_t(kt_per * kTilePanels);
+        a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
         const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
         dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
@@ -628,7 +650,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         if (splits > 1) {
             const int64_t total = t.M * L.N;
             k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, t.M, L.N, t.Y, t.ldy,
-                                                                        t.ydtype, 0);
+                                                                        t.ydtype, t.pix);
         }
         return hip_status(hipGetLastError());
     } else {

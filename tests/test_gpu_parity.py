@@ -119,6 +119,11 @@ GEMM_CASES = [
     (5, 37, 200, 4, "f32", 0.4, 0.3),
     (70, 64, 512, 8, "f32", 0.3, 0.3),
     (130, 130, 1024, 16, "f32", 0.6, 0.2),
+    # the pipelined kernel (M > 16, K a whole number of 64-wide panels) on K ranges shorter than its pipeline
+    (40, 48, 64, 8, "bf16", 0.5, 0.4),
+    (130, 130, 128, 16, "bf16", 0.7, 0.2),
+    (300, 200, 192, 8, "bf16", 0.4, 0.5),
+    (257, 129, 320, 8, "bf16", 0.5, 0.3),
 ]
 
 
@@ -233,6 +238,11 @@ CONV_CASES = [
     (2, 32, 14, 14, 48, 1, 2, 0, 8, "bf16"),
     (2, 8, 6, 5, 18, 3, 1, 1, 4, "f32"),
     (1, 16, 8, 8, 16, 3, 1, 0, 8, "f32"),
+    # 1x1 without padding on whole 64-channel panels: gathered pixels through the pipelined GEMM kernel
+    (2, 128, 9, 9, 72, 1, 2, 0, 8, "bf16"),       # stride 2: 5 x 5 sampled pixels, M = 50
+    (3, 192, 12, 12, 136, 1, 1, 0, 8, "bf16"),    # M = 432: the 256-row tile, two column tiles
+    (2, 64, 10, 6, 24, 1, 2, 0, 16, "bf16"),      # 15 output pixels per image: unaligned NCHW stores
+    (1, 64, 1, 1, 16, 1, 1, 0, 8, "bf16"),        # one pixel
 ]
 
 
