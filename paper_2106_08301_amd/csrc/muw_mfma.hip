@@ -75,6 +75,35 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict
     }
 }
 
+// The same copy for whole images whose pixel count and channel count are multiples of 8 (16-byte
+// aligned rows on both sides): 16-byte global loads (8 pixels of a channel) and stores (8 channels of a
+// pixel); the transposition happens in LDS, written 2 bytes at a time and read back as dwords.
+__global__ __launch_bounds__(256) void k_nchw_to_nhwc_x8(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                         int C, int P)
+{
+    __shared__ uint16_t t[64][66];  // [pixel][channel]; 33-dword rows spread the 2-byte writes over the banks
+    const int64_t b = blockIdx.z;
+    const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
+    const int grp = threadIdx.x & 7, row = threadIdx.x >> 3;  // 8 groups of 8 along the fast axis, 32 rows per pass
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int c = c0 + row + 32 * half, pg = p0 + 8 * grp;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (c < C && pg < P) v = *reinterpret_cast<const uint4 *>(src + (b * C + c) * int64_t(P) + pg);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[8 * grp + i][row + 32 * half] = uint16_t(w[i >> 1] >> (16 * (i & 1)));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int q = p0 + row + 32 * half, cg = c0 + 8 * grp;
+        if (q >= P || cg >= C) continue;
+        const uint32_t *r = reinterpret_cast<const uint32_t *>(&t[row + 32 * half][8 * grp]);
+        *reinterpret_cast<uint4 *>(dst + (b * int64_t(P) + q) * C + cg) = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
 template <int B, int TM, bool CONV>
 __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layout L)
 {
@@ -355,6 +384,18 @@ bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
     return true;
 }
 
+// NCHW -> NHWC staging of the input (step > 1: only the pixels a strided 1x1 convolution reads)
+void launch_nchw_to_nhwc(const ConvArgs &c, int Cin, int OH, int OW, int step, void *dst, hipStream_t st)
+{
+    const int P = OH * OW;
+    dim3 tg(unsigned((P + 63) / 64), unsigned((Cin + 63) / 64), unsigned(c.Nb));
+    const uint16_t *src = static_cast<const uint16_t *>(c.X);
+    if (step == 1 && P % 8 == 0 && Cin % 8 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0)
+        k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P);
+    else
+        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step);
+}
+
 // 1x1, no padding (any stride): every output pixel reads exactly one input pixel
 bool conv_is_pointwise(const muw_desc &d, const ConvArgs &a) { return d.KH == 1 && d.KW == 1 && a.pad == 0; }
 
@@ -377,9 +418,7 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     if (conv_is_pointwise(d, c)) {
         // a 1x1 convolution without padding is a linear layer over the (sampled) pixels
         const int P = int(c.OH * c.OW);
-        dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
-        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin,
-                                          int(c.H), int(c.W), int(c.OH), int(c.OW), c.stride);
+        launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
         TileGemmArgs a{};
         a.blob = static_cast<const uint8_t *>(c.blob);
         a.X = static_cast<const uint16_t *>(ws);
@@ -399,10 +438,7 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         default: break;
         }
     }
-    const int P = int(c.H * c.W);
-    dim3 tg(unsigned((P + 63) / 64), unsigned((d.Cin + 63) / 64), unsigned(c.Nb));
-    k_nchw_to_nhwc<<<tg, 256, 0, st>>>(static_cast<const uint16_t *>(c.X), static_cast<uint16_t *>(ws), d.Cin,
-                                      int(c.H), int(c.W), int(c.H), int(c.W), 1);
+    launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st);
     TileGemmArgs a{};
     a.blob = static_cast<const uint8_t *>(c.blob);
     a.X = static_cast<const uint16_t *>(ws);

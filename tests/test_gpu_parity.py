@@ -230,6 +230,17 @@ def test_small_m_kernel_long_walk_over_several_matrices(muw, oracle):
         check_close(to_f64(Ys[g]), oracle.gemm(Xg[g].f64(), What))
 
 
+def test_pointwise_conv_bf16_output(muw, oracle):
+    case = synth.ConvCase("t", 2, 64, 8, 8, 48, 1, 1, 1, 0, 8, 0.5, 0.4, "bf16", 655)
+    X, Wt = synth.make_conv(case)
+    (_, _, _, What), _ = oracle_encode(oracle, Wt, 8, 0.5, 0.4)
+    Y_ref = oracle.conv2d(X.f64(), What, 1, 1, 1, 0)
+    layer = muw.muw_encode(to_device(Wt), 8, 0.5, 0.4)
+    Y = muw.muw_conv2d(layer, to_device(X), 1, 0, out_dtype=torch.bfloat16)
+    Y_ref_b = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(Y_ref.astype(np.float32))).reshape(Y_ref.shape)
+    check_close(to_f64(Y), Y_ref_b, rel=1e-3, mx=1e-2)
+
+
 CONV_CASES = [
     # Nb, Cin, H, W, Cout, ks, stride, pad, B, dtype
     (2, 16, 9, 10, 20, 3, 1, 1, 4, "bf16"),
