@@ -24,7 +24,9 @@
  * Parity pins (tests/test_oracle_pins.py): brute-force projection on tiny blocks, brute-force
  * subset selection, Table 1 reductions, the Fig. 1 parameter counts, the ResNet-50 MAC estimates of
  * Sec. 4.5, closed-form Gaussian statistics, dense/all-pruned special cases of the GEMM, im2col and
- * library convolution for the conv.  No function in this file is "parity unpinned".
+ * library convolution for the conv; for the ADMM steps the unconstrained and the feasible special
+ * cases, the dual variable as the running sum of residuals, finite differences of the penalty, and
+ * the brute-force projection again.  No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -227,6 +229,53 @@ done:
     free(e_u);
     free(order);
     return rc;
+}
+
+/* The Q-step and the U-step of one ADMM iteration for one layer in GEMM view (Sec. 3.3, Alg. 1 steps 6
+ * and 7; Eq. 6 and Eq. 7).  Every array holds stored values (fp32 or bf16) exactly as doubles, and every
+ * arithmetic result is rounded once to the storage type, as a training loop in that type would:
+ *   T     = round(W + U)                       the point that is projected
+ *   Q     = Unify(T)                           the projection of oracle_encode (same selection, q, signs)
+ *   U_new = round(round(U + W) - Q)            the accumulated dual variable
+ * tags[NB] receives the block tags of the projection.  Returns what oracle_encode returns. */
+int oracle_admm_update(const double *W, const double *U, int64_t N, int64_t K, int64_t B, int64_t n_u,
+                       int64_t n_p, int storage, double *Q, double *U_new, uint8_t *tags)
+{
+    if (N <= 0 || K <= 0 || B <= 0 || K % B != 0) return -1;
+    int64_t n = N * K, NB = n / B;
+    double *T = (double *)malloc(sizeof(double) * (size_t)n);
+    uint16_t *signs = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)NB);
+    double *mags = (double *)malloc(sizeof(double) * (size_t)NB);
+    for (int64_t i = 0; i < n; ++i) T[i] = oracle_round_to_storage(W[i] + U[i], storage);
+    int rc = oracle_encode(T, N, K, B, n_u, n_p, storage, tags, signs, mags, Q);
+    if (rc == 0)
+        for (int64_t i = 0; i < n; ++i) {
+            double uw = oracle_round_to_storage(U[i] + W[i], storage);
+            U_new[i] = oracle_round_to_storage(uw - Q[i], storage);
+        }
+    free(T);
+    free(signs);
+    free(mags);
+    return rc;
+}
+
+/* The quadratic term of the augmented Lagrangian (Eq. 4) for one layer and its gradient with respect
+ * to W (what step 4 of Alg. 1 adds to the loss gradient):
+ *   P = rho / 2 * sum_i (W_i - Q_i + U_i)^2            in double
+ *   G_i = round32(rho * round32(round32(W_i - Q_i) + U_i))   fp32 arithmetic, left to right
+ * rho is an fp32 value.  G may be NULL. */
+double oracle_admm_penalty(const double *W, const double *Q, const double *U, int64_t n, double rho, double *G)
+{
+    double P = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double d = W[i] - Q[i] + U[i];
+        P += d * d;
+        if (G) {
+            double d32 = (double)(float)((double)(float)(W[i] - Q[i]) + U[i]);
+            G[i] = (double)(float)(rho * d32);
+        }
+    }
+    return 0.5 * rho * P;
 }
 
 /* Y[m][n] = sum_k X[m][k] * What[n][k]  (Sec. 3.2: the layer as a GEMM), k ascending, in double.

@@ -44,6 +44,10 @@ def lib():
         L.oracle_counters.argtypes = [i64, i64, i64, i64, i64, C.POINTER(i64), C.POINTER(i64),
                                       C.POINTER(i64)]
         L.oracle_counters.restype = None
+        L.oracle_admm_update.argtypes = [p, p, i64, i64, i64, i64, i64, C.c_int, p, p, p]
+        L.oracle_admm_update.restype = C.c_int
+        L.oracle_admm_penalty.argtypes = [p, p, p, i64, dbl, p]
+        L.oracle_admm_penalty.restype = dbl
         L.oracle_omp_threads.argtypes = []
         L.oracle_omp_threads.restype = C.c_int
         _lib = L
@@ -115,6 +119,33 @@ def encode(Wg, B, n_u, n_p, storage):
     if rc != 0:
         raise ValueError("bad arguments")
     return tags, signs, mags, What
+
+
+def admm_update(W, U, B, n_u, n_p, storage):
+    """Q-step and U-step of one ADMM iteration (Alg. 1, steps 6 and 7).  Returns (Q, U_new, tags)."""
+    W, U = _f64(W), _f64(U)
+    N, K = W.shape
+    if U.shape != W.shape or B <= 0 or K % B:
+        raise ValueError("bad shapes")
+    Q = np.empty((N, K), dtype=np.float64)
+    U_new = np.empty((N, K), dtype=np.float64)
+    tags = np.empty(N * K // B, dtype=np.uint8)
+    rc = lib().oracle_admm_update(_ptr(W), _ptr(U), N, K, B, int(n_u), int(n_p), int(storage), _ptr(Q),
+                                  _ptr(U_new), _ptr(tags))
+    if rc == -2:
+        raise ValueError("non-finite weight")
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return Q, U_new, tags
+
+
+def admm_penalty(W, Q, U, rho, want_grad=True):
+    """Returns (P, G): the quadratic term rho/2 ||W - Q + U||_F^2 of Eq. 4 and its fp32 gradient in W."""
+    W, Q, U = _f64(W), _f64(Q), _f64(U)
+    G = np.empty(W.shape, dtype=np.float64) if want_grad else None
+    P = lib().oracle_admm_penalty(_ptr(W), _ptr(Q), _ptr(U), W.size, float(np.float32(rho)),
+                                  _ptr(G) if want_grad else None)
+    return P, G
 
 
 def gemm(X, What):

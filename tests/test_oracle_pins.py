@@ -418,3 +418,85 @@ def test_conv_with_encoded_weights_blocks_run_along_cin(oracle):
         src = Wt[co, cb * B:(cb + 1) * B, kh, kw]
         assert np.allclose(np.abs(blk), np.abs(src).mean(), rtol=1e-6)
         assert np.all(np.sign(blk) == np.sign(src))
+
+
+# ---- ADMM steps (Sec. 3.3: Alg. 1, Eq. 4, 6, 7) ---------------------------------------------------
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+def test_admm_update_without_constraints_copies_the_sum_and_clears_the_dual(oracle):
+    # nothing constrained: the projection is the identity, so Q = W + U (rounded) and U_new = (U + W) - Q = 0
+    W, U = f32(rng_matrix(31, 6, 16)), f32(rng_matrix(32, 6, 16, 0.1))
+    Q, U_new, tags = oracle.admm_update(W, U, 4, 0, 0, oracle.STORE_F32)
+    assert np.array_equal(Q, (W.astype(np.float32) + U.astype(np.float32)).astype(np.float64))
+    assert not U_new.any() and not tags.any()
+
+
+def test_admm_update_of_a_feasible_point_is_a_fixed_point(oracle):
+    # W already in the constraint set and U = 0: Q = W and the dual stays zero (Alg. 1 would stop moving)
+    W0 = f32(rng_matrix(33, 8, 32))
+    n_u, n_p = oracle.counts(8 * 32 // 8, 0.5, 0.25)
+    W = oracle.encode(W0, 8, n_u, n_p, oracle.STORE_F32)[3]
+    Q, U_new, _ = oracle.admm_update(W, np.zeros_like(W), 8, n_u, n_p, oracle.STORE_F32)
+    assert np.array_equal(Q, W) and not U_new.any()
+
+
+def test_admm_projection_is_the_nearest_feasible_point_bruteforce(oracle):
+    # Eq. 6: Q minimises ||W + U - Q||_F over the constraint set.  With unification only the set is "n_u
+    # of the NB blocks are unified" and the best value of a unified block is +-mean|t|: try every subset.
+    N, K, B, n_u = 2, 6, 2, 3
+    W, U = f32(rng_matrix(34, N, K)), f32(rng_matrix(35, N, K, 0.3))
+    Q, _, _ = oracle.admm_update(W, U, B, n_u, 0, oracle.STORE_F32)
+    T = (W.astype(np.float32) + U.astype(np.float32)).astype(np.float64)
+    blocks = T.reshape(-1, B)
+    best = math.inf
+    for chosen in itertools.combinations(range(len(blocks)), n_u):
+        cost = sum(((np.abs(blocks[j]) - np.abs(blocks[j]).mean()) ** 2).sum() for j in chosen)
+        best = min(best, cost)
+    assert ((T - Q) ** 2).sum() == pytest.approx(best, rel=1e-6)
+
+
+def test_admm_dual_variable_is_the_running_sum_of_residuals(oracle):
+    # Eq. 7 unrolled: U_k = sum_{i <= k} (W_i - Q_i).  The W-step of the quadratic loss
+    # f(W) = 1/2 ||W - A||^2 has the closed form W = (A + rho (Q - U)) / (1 + rho).
+    A = f32(rng_matrix(36, 6, 24))
+    n_u, n_p = oracle.counts(6 * 24 // 4, 0.6, 0.2)
+    rho = 2.0    # (a large enough penalty: the constraint set is not convex, a small one need not converge)
+    Q = oracle.encode(A, 4, n_u, n_p, oracle.STORE_F32)[3]        # Alg. 1 step 1
+    U = np.zeros_like(A)
+    acc = np.zeros_like(A)
+    res = []
+    for _ in range(24):
+        W = f32((A + rho * (Q - U)) / (1.0 + rho))
+        Q, U, _ = oracle.admm_update(W, U, 4, n_u, n_p, oracle.STORE_F32)
+        acc += W - Q
+        res.append(np.linalg.norm(W - Q))
+        assert np.allclose(U, acc, rtol=0, atol=1e-5)
+    assert res[-1] < 1e-3 * res[0]       # the iterates reach the constraint set
+
+
+def test_admm_penalty_gradient_matches_finite_differences(oracle):
+    W, Q, U = f32(rng_matrix(37, 3, 8)), f32(rng_matrix(38, 3, 8)), f32(rng_matrix(39, 3, 8, 0.2))
+    rho = 0.375
+    P, G = oracle.admm_penalty(W, Q, U, rho)
+    assert P == pytest.approx(0.5 * rho * ((W - Q + U) ** 2).sum(), rel=1e-12)
+    h = 1e-4
+    for idx in [(0, 0), (1, 5), (2, 7)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += h
+        Wm[idx] -= h
+        num = (oracle.admm_penalty(Wp, Q, U, rho, False)[0] - oracle.admm_penalty(Wm, Q, U, rho, False)[0]) / (2 * h)
+        assert G[idx] == pytest.approx(num, rel=1e-5, abs=1e-6)
+    assert np.array_equal(G, G.astype(np.float32).astype(np.float64))     # an fp32 gradient
+
+
+def test_admm_update_in_bf16_rounds_every_step_to_bf16(oracle):
+    W = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(rng_matrix(40, 4, 16).astype(np.float32))).reshape(4, 16)
+    U = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(rng_matrix(41, 4, 16, 0.05).astype(np.float32))).reshape(4, 16)
+    Q, U_new, _ = oracle.admm_update(W, U, 8, 0, 0, oracle.STORE_BF16)
+    T = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits((W + U).astype(np.float32))).reshape(4, 16)
+    assert np.array_equal(Q, T)
+    for a in (Q, U_new):
+        assert np.array_equal(a, synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(a.astype(np.float32))).reshape(a.shape))
