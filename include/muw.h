@@ -96,6 +96,28 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
                       double r_prune, void *blob_dev, size_t blob_bytes, void *ws_dev,
                       size_t ws_bytes, void *hip_stream);
 
+/* ---- ADMM training steps for one layer (Sec. 3.3).  The training loop itself (loss, optimiser, data)
+ * is the caller's; these are the steps of Alg. 1 that need the projection Unify().  W, U, Q are dense
+ * tensors in `layout` (MUW_LAYOUT_NK [N][K] or MUW_LAYOUT_OIHW), dtype desc->wdtype, 16-byte aligned,
+ * caller-owned.  Arithmetic is fp32 and every result is rounded once to desc->wdtype. */
+
+/* Workspace muw_admm_update needs.  Host only. */
+size_t muw_admm_workspace_bytes(const muw_desc *desc);
+
+/* Alg. 1 steps 6 and 7 (Eq. 6, Eq. 7):  Q = Unify(W + U) -- the projection muw_encode performs (same
+ * block selection at these ratios, same magnitudes and signs), written out dense: +-q^ in unified
+ * blocks, 0 in pruned blocks, the value of W + U elsewhere -- then U <- (U + W) - Q in place.
+ * Waits for the stream before returning.  MUW_ENONFINITE (Q and U undefined) if W + U has a NaN/Inf. */
+muw_status muw_admm_update(const muw_desc *desc, const void *W_dev, void *U_dev, void *Q_dev,
+                           muw_layout layout, double r_unify, double r_prune, void *ws_dev,
+                           size_t ws_bytes, void *hip_stream);
+
+/* Alg. 1 step 4 (Eq. 4): G[i] = rho * ((W[i] - Q[i]) + U[i]), i < count, the gradient with respect to W of
+ * the quadratic term rho/2 ||W - Q + U||_F^2 of the augmented Lagrangian.  W, Q, U of `dtype`, G fp32.
+ * Asynchronous on the stream. */
+muw_status muw_admm_penalty_grad(int64_t count, const void *W_dev, const void *Q_dev, const void *U_dev,
+                                 muw_dtype dtype, float rho, float *G_dev, void *hip_stream);
+
 /* Layout-independent view of an encoded layer, for bit-exact comparison: tags_dev[NB] (muw_tag),
  * signs_dev[NB] (bit l = w_l < 0; 0 unless UNIFIED), mags_dev[NB] (stored magnitude in wdtype; 0 unless
  * UNIFIED).  Any of the three may be NULL. */

@@ -19,7 +19,8 @@ MUW_LAYOUT_NK, MUW_LAYOUT_OIHW = 0, 1
 
 EXPORTED = ["muw_version", "muw_status_str", "muw_counts", "muw_encode_sizes", "muw_encode", "muw_export",
             "muw_decode", "muw_compressed_bytes", "muw_gemm_workspace_bytes", "muw_gemm",
-            "muw_gemm_grouped", "muw_conv2d_workspace_bytes", "muw_conv2d"]
+            "muw_gemm_grouped", "muw_conv2d_workspace_bytes", "muw_conv2d", "muw_admm_workspace_bytes",
+            "muw_admm_update", "muw_admm_penalty_grad"]
 
 
 class muw_desc(C.Structure):
@@ -58,8 +59,12 @@ def _load():
     L.muw_conv2d_workspace_bytes.argtypes = [dp, i64, i64, i64, i32, i32]
     L.muw_conv2d_workspace_bytes.restype = sz
     L.muw_conv2d.argtypes = [dp, vp, vp, C.c_int, i64, i64, i64, i32, i32, vp, C.c_int, vp, sz, vp]
+    L.muw_admm_workspace_bytes.argtypes = [dp]
+    L.muw_admm_workspace_bytes.restype = sz
+    L.muw_admm_update.argtypes = [dp, vp, vp, vp, C.c_int, dbl, dbl, vp, sz, vp]
+    L.muw_admm_penalty_grad.argtypes = [i64, vp, vp, vp, C.c_int, C.c_float, vp, vp]
     for name in ("muw_counts", "muw_encode_sizes", "muw_encode", "muw_export", "muw_decode", "muw_gemm",
-                 "muw_gemm_grouped", "muw_conv2d"):
+                 "muw_gemm_grouped", "muw_conv2d", "muw_admm_update", "muw_admm_penalty_grad"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -150,6 +155,38 @@ def muw_encode(W, B, r_unify, r_prune):
     _check(lib.muw_encode(C.byref(desc), _ptr(W), layout, r_unify, r_prune, _ptr(blob), blob_bytes,
                           _ptr(ws), ws_bytes, _stream()), "muw_encode")
     return EncodedLayer(desc, blob)
+
+
+def _desc_for(W, B):
+    if W.dim() == 2:
+        N, K = W.shape
+        return make_desc(N, K, B, _dtype_code(W)), MUW_LAYOUT_NK
+    if W.dim() == 4:
+        Cout, Cin, KH, KW = W.shape
+        return make_desc(Cout, Cin * KH * KW, B, _dtype_code(W), KH, KW, Cin), MUW_LAYOUT_OIHW
+    raise ValueError("W must be 2-D or 4-D")
+
+
+def muw_admm_update(W, U, B, r_unify, r_prune):
+    """Q-step and U-step of one ADMM iteration: returns Q = Unify(W + U); U is updated in place."""
+    assert W.is_cuda and W.is_contiguous() and U.is_contiguous() and U.shape == W.shape and U.dtype == W.dtype
+    desc, layout = _desc_for(W, B)
+    Q = torch.empty_like(W)
+    ws_bytes = lib.muw_admm_workspace_bytes(C.byref(desc))
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=W.device)
+    _check(lib.muw_admm_update(C.byref(desc), _ptr(W), _ptr(U), _ptr(Q), layout, r_unify, r_prune, _ptr(ws),
+                               ws_bytes, _stream()), "muw_admm_update")
+    return Q
+
+
+def muw_admm_penalty_grad(W, Q, U, rho):
+    """rho * (W - Q + U) as an fp32 tensor of W's shape."""
+    assert W.is_cuda and W.is_contiguous() and Q.is_contiguous() and U.is_contiguous()
+    assert Q.shape == W.shape and U.shape == W.shape and Q.dtype == W.dtype and U.dtype == W.dtype
+    G = torch.empty(W.shape, dtype=torch.float32, device=W.device)
+    _check(lib.muw_admm_penalty_grad(W.numel(), _ptr(W), _ptr(Q), _ptr(U), _dtype_code(W), float(rho), _ptr(G),
+                                     _stream()), "muw_admm_penalty_grad")
+    return G
 
 
 def muw_export(layer):

@@ -116,6 +116,42 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
     return MUW_OK;
 }
 
+size_t muw_admm_workspace_bytes(const muw_desc *desc)
+{
+    if (check_desc(desc) != MUW_OK) return 0;
+    return admm_workspace_bytes(*desc, layout_of(desc));
+}
+
+muw_status muw_admm_update(const muw_desc *desc, const void *W_dev, void *U_dev, void *Q_dev, muw_layout layout,
+                           double r_unify, double r_prune, void *ws_dev, size_t ws_bytes, void *hip_stream)
+{
+    muw_status rc = check_desc(desc);
+    if (rc != MUW_OK) return rc;
+    if (!W_dev || !U_dev || !Q_dev || !ws_dev) return MUW_EINVAL;
+    if (layout != MUW_LAYOUT_NK && layout != MUW_LAYOUT_OIHW) return MUW_EINVAL;
+    if (!aligned16(W_dev) || !aligned16(U_dev) || !aligned16(Q_dev) || !aligned16(ws_dev)) return MUW_EINVAL;
+    const Layout L = layout_of(desc);
+    if (ws_bytes < admm_workspace_bytes(*desc, L)) return MUW_ENOSPC;
+    int64_t n_u, n_p;
+    rc = muw_counts(L.N * L.KB, r_unify, r_prune, &n_u, &n_p);
+    if (rc != MUW_OK) return rc;
+    bool nonfinite = false;
+    rc = launch_admm_update(*desc, L, W_dev, U_dev, Q_dev, int(layout), n_u, n_p, ws_dev,
+                            static_cast<hipStream_t>(hip_stream), &nonfinite);
+    if (rc != MUW_OK) return rc;
+    return nonfinite ? MUW_ENONFINITE : MUW_OK;
+}
+
+muw_status muw_admm_penalty_grad(int64_t count, const void *W_dev, const void *Q_dev, const void *U_dev,
+                                 muw_dtype dtype, float rho, float *G_dev, void *hip_stream)
+{
+    if (count < 0 || !valid_dtype(dtype)) return MUW_EINVAL;
+    if (count == 0) return MUW_OK;
+    if (!W_dev || !Q_dev || !U_dev || !G_dev) return MUW_EINVAL;
+    return launch_admm_penalty_grad(count, W_dev, Q_dev, U_dev, int(dtype), rho, G_dev,
+                                    static_cast<hipStream_t>(hip_stream));
+}
+
 muw_status muw_export(const muw_desc *desc, const void *blob_dev, uint8_t *tags_dev, uint16_t *signs_dev,
                       void *mags_dev, void *hip_stream)
 {

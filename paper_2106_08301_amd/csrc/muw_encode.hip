@@ -11,6 +11,7 @@
 //            then ties at the threshold value are taken in block-index order via a prefix count
 //   pack     per tile: count, prefix-sum the tile sizes into the directory, then one wavefront per
 //            tile writes masks, magnitudes, permuted sign bits and dense payload
+#include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
 namespace muw {
@@ -600,7 +601,149 @@ void decode_typed(const Layout &L, const void *blob, void *What, hipStream_t st)
                                                             static_cast<T *>(What));
 }
 
+// ---- ADMM steps (Sec. 3.3, Alg. 1): the projection above without the packing, and the two
+//      elementwise updates around it.  Arithmetic in fp32, every result rounded once to the storage type.
+__device__ inline float as_f32(float v) { return v; }
+__device__ inline float as_f32(bf16_t v) { return __uint_as_float(uint32_t(v.bits) << 16); }
+__device__ inline void put_f32(float *dst, float v) { *dst = v; }
+__device__ inline void put_f32(bf16_t *dst, float v) { dst->bits = f32_to_bf16_rne(v); }
+
+// T = W + U: the point the Q-step projects (Alg. 1 step 6)
+template <typename T>
+__global__ __launch_bounds__(256) void k_admm_sum(const T *W, const T *U, T *sum, int64_t n)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) put_f32(&sum[i], as_f32(W[i]) + as_f32(U[i]));
+}
+
+// Q = Unify(T) from the block tags (Eq. 2 with the magnitude of Sec. 3.1, rounded once to the storage
+// type) and U <- (U + W) - Q (Eq. 7), one thread per block.
+template <typename T, int B>
+__global__ __launch_bounds__(256) void k_admm_project(const T *sum, const T *W, T *U, T *Q, const uint8_t *tags,
+                                                      int layout, int64_t N, int64_t K, int Cin, int KH, int KW)
+{
+    const int64_t KB = K / B;
+    const int64_t j = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= N * KB) return;
+    const int64_t n = j / KB, kb = j % KB;
+    T raw[B];
+    load_block<T, B>(sum, layout, n, kb, K, Cin, KH, KW, raw);
+    int64_t first, step;  // element l of the block sits at first + l * step in all four tensors
+    if (layout == MUW_LAYOUT_NK) {
+        first = n * K + kb * B;
+        step = 1;
+    } else {
+        const int64_t k = kb * B, tap = k / Cin, cin = k % Cin;
+        first = ((n * Cin + cin) * KH + tap / KW) * KW + tap % KW;
+        step = int64_t(KH) * KW;
+    }
+    const uint8_t tag = tags[j];
+    T mag;
+    store_mag(&mag, block_q<T, B>(raw));
+    const float q = as_f32(mag);
+#pragma unroll
+    for (int l = 0; l < B; ++l) {
+        const int64_t i = first + l * step;
+        float v = as_f32(raw[l]);
+        if (tag == MUW_TAG_UNIFIED)
+            v = widen(raw[l]) < 0.0 ? -q : q;
+        else if (tag == MUW_TAG_PRUNED)
+            v = 0.f;
+        T qv;
+        put_f32(&qv, v);
+        Q[i] = qv;
+        T uw;
+        put_f32(&uw, as_f32(U[i]) + as_f32(W[i]));
+        put_f32(&U[i], as_f32(uw) - as_f32(qv));
+    }
+}
+
+// G = rho (W - Q + U): gradient in W of the quadratic term of the augmented Lagrangian (Eq. 4)
+template <typename T>
+__global__ __launch_bounds__(256) void k_admm_penalty_grad(const T *W, const T *Q, const T *U, float rho, float *G,
+                                                           int64_t n)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float d = as_f32(W[i]) - as_f32(Q[i]);
+    const float e = d + as_f32(U[i]);
+    G[i] = rho * e;
+}
+
+template <typename T, int B>
+muw_status admm_update_typed(const muw_desc &d, const Layout &L, const void *W, void *U, void *Q, int layout,
+                             int64_t n_u, int64_t n_p, uint8_t *ws, hipStream_t st, bool *nonfinite)
+{
+    const EncodeWorkspace w = encode_workspace(L);
+    const int64_t NB = L.N * L.KB, n = L.N * L.K;
+    uint64_t *key_p = reinterpret_cast<uint64_t *>(ws + w.key_p_off);
+    uint64_t *key_u = reinterpret_cast<uint64_t *>(ws + w.key_u_off);
+    uint8_t *tags = ws + w.tags_off;
+    SelState *state = reinterpret_cast<SelState *>(ws + w.state_off);
+    uint32_t *chunks = reinterpret_cast<uint32_t *>(ws + w.chunk_off);
+    T *sum = reinterpret_cast<T *>(ws + w.total);
+
+    if (hipMemsetAsync(tags, MUW_TAG_DENSE, size_t(NB), st) != hipSuccess) return MUW_EHIP;
+    if (hipMemsetAsync(state, 0, sizeof(SelState), st) != hipSuccess) return MUW_EHIP;
+    k_admm_sum<T><<<unsigned((n + 255) / 256), 256, 0, st>>>(static_cast<const T *>(W), static_cast<const T *>(U),
+                                                             sum, n);
+    const unsigned grid_blocks = unsigned((NB + 255) / 256);
+    k_scores<T, B><<<grid_blocks, 256, 0, st>>>(sum, layout, L.N, L.K, d.Cin, d.KH, d.KW, key_p, key_u, state);
+    muw_status rc = select_smallest(key_p, NB, n_p, state, chunks, tags, MUW_TAG_PRUNED, key_u, 1, st);
+    if (rc != MUW_OK) return rc;
+    rc = select_smallest(key_u, NB, n_u, state, chunks, tags, MUW_TAG_UNIFIED, nullptr, 0, st);
+    if (rc != MUW_OK) return rc;
+    k_admm_project<T, B><<<grid_blocks, 256, 0, st>>>(sum, static_cast<const T *>(W), static_cast<T *>(U),
+                                                      static_cast<T *>(Q), tags, layout, L.N, L.K, d.Cin, d.KH,
+                                                      d.KW);
+    if (hipGetLastError() != hipSuccess) return MUW_EHIP;
+    uint32_t bad = 0;
+    if (hipMemcpyAsync(&bad, &state->nonfinite, sizeof(bad), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return MUW_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MUW_EHIP;
+    *nonfinite = bad != 0;
+    return MUW_OK;
+}
+
 }  // namespace
+
+size_t admm_workspace_bytes(const muw_desc &d, const Layout &L)
+{
+    return size_t(encode_workspace(L).total + align16(uint64_t(L.N) * uint64_t(L.K) * uint64_t(value_bytes(d.wdtype))));
+}
+
+muw_status launch_admm_update(const muw_desc &d, const Layout &L, const void *W, void *U, void *Q, int layout,
+                              int64_t n_u, int64_t n_p, void *ws, hipStream_t st, bool *nonfinite)
+{
+    uint8_t *w = static_cast<uint8_t *>(ws);
+#define MUW_ADMM_CASE(T, BB) \
+    if (d.B == BB) return admm_update_typed<T, BB>(d, L, W, U, Q, layout, n_u, n_p, w, st, nonfinite)
+    if (d.wdtype == MUW_BF16) {
+        MUW_ADMM_CASE(bf16_t, 4);
+        MUW_ADMM_CASE(bf16_t, 8);
+        MUW_ADMM_CASE(bf16_t, 16);
+    } else {
+        MUW_ADMM_CASE(float, 4);
+        MUW_ADMM_CASE(float, 8);
+        MUW_ADMM_CASE(float, 16);
+    }
+#undef MUW_ADMM_CASE
+    return MUW_EUNSUPPORTED;
+}
+
+muw_status launch_admm_penalty_grad(int64_t n, const void *W, const void *Q, const void *U, int dtype, float rho,
+                                    float *G, hipStream_t st)
+{
+    if (n == 0) return MUW_OK;
+    const unsigned grid = unsigned((n + 255) / 256);
+    if (dtype == MUW_BF16)
+        k_admm_penalty_grad<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t *>(W), static_cast<const bf16_t *>(Q),
+                                                          static_cast<const bf16_t *>(U), rho, G, n);
+    else
+        k_admm_penalty_grad<float><<<grid, 256, 0, st>>>(static_cast<const float *>(W), static_cast<const float *>(Q),
+                                                         static_cast<const float *>(U), rho, G, n);
+    return hip_status(hipGetLastError());
+}
 
 EncodeWorkspace encode_workspace(const Layout &L)
 {

@@ -29,6 +29,13 @@ muw_status launch_export(const muw_desc &d, const Layout &L, const void *blob, u
 muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, void *What,
                          hipStream_t st);
 
+// ADMM steps (Sec. 3.3): projection of W + U written out dense, dual update, penalty gradient
+size_t admm_workspace_bytes(const muw_desc &d, const Layout &L);
+muw_status launch_admm_update(const muw_desc &d, const Layout &L, const void *W, void *U, void *Q, int layout,
+                              int64_t n_u, int64_t n_p, void *ws, hipStream_t st, bool *nonfinite);
+muw_status launch_admm_penalty_grad(int64_t n, const void *W, const void *Q, const void *U, int dtype, float rho,
+                                    float *G, hipStream_t st);
+
 struct GemmArgs {
     const void *blob;        // single problem
     const void *X;

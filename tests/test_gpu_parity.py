@@ -266,3 +266,45 @@ def test_conv2d_matches_oracle(muw, oracle, Nb, Cin, H, W, Cout, ks, stride, pad
     layer = muw.muw_encode(to_device(Wt), B, 0.5, 0.4)
     Y = muw.muw_conv2d(layer, to_device(X), stride, pad)
     check_close(to_f64(Y), Y_ref)
+
+
+# ---- ADMM steps (Sec. 3.3): bit-exact against the oracle ------------------------------------------
+
+ADMM_CASES = [
+    # shape, B, dtype, r_u, r_p
+    ((48, 256), 4, "f32", 0.5, 0.25),
+    ((33, 1552), 16, "bf16", 0.7, 0.25),
+    ((130, 96), 8, "f32", 0.6, 0.2),
+    ((24, 32, 3, 3), 8, "bf16", 0.5, 0.4),     # OIHW: blocks run along Cin
+    ((20, 16, 3, 3), 4, "f32", 0.4, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape,B,dtype,r_u,r_p", ADMM_CASES)
+def test_admm_update_and_penalty_gradient_are_bit_exact(muw, oracle, shape, B, dtype, r_u, r_p):
+    W = synth.normal_tensor(1200 + B, shape, 0.05, dtype, stream=1)
+    U = synth.normal_tensor(1300 + B, shape, 0.01, dtype, stream=2)
+    Wd, Ud = W.f64(), U.f64()
+    Wg = oracle.conv_weight_gemm_view(Wd) if Wd.ndim == 4 else Wd
+    Ug = oracle.conv_weight_gemm_view(Ud) if Ud.ndim == 4 else Ud
+    n_u, n_p = oracle.counts(Wg.size // B, r_u, r_p)
+    Q_o, U_o, _ = oracle.admm_update(Wg, Ug, B, n_u, n_p, storage_code(dtype, oracle))
+    if Wd.ndim == 4:
+        Q_o = oracle.gemm_view_to_conv_weight(Q_o, shape[1], shape[2], shape[3])
+        U_o = oracle.gemm_view_to_conv_weight(U_o, shape[1], shape[2], shape[3])
+    W_dev, U_dev = to_device(W), to_device(U)
+    Q_dev = muw.muw_admm_update(W_dev, U_dev, B, r_u, r_p)
+    assert np.array_equal(to_f64(Q_dev), Q_o.reshape(shape))
+    assert np.array_equal(to_f64(U_dev), U_o.reshape(shape))
+    rho = 0.375
+    _, G_o = oracle.admm_penalty(Wd, Q_o.reshape(shape), U_o.reshape(shape), rho)
+    G = muw.muw_admm_penalty_grad(W_dev, Q_dev, U_dev, rho)
+    assert np.array_equal(to_f64(G), G_o)
+
+
+def test_admm_update_refuses_non_finite(muw):
+    W = torch.ones((16, 64), dtype=torch.float32, device="cuda")
+    U = torch.zeros_like(W)
+    U[3, 5] = float("inf")
+    with pytest.raises(muw.MuwError):
+        muw.muw_admm_update(W, U, 8, 0.5, 0.25)
