@@ -6,6 +6,8 @@
 //                   16 weights of a panel directly into the MFMA B-operand registers and reads the
 //                   matching activations straight from global memory.  General (any M, N, K, ld,
 //                   alignment, linear or convolution gather); the reference kernel of the library.
+#include <algorithm>
+
 #include "muw_decode.hpp"
 #include "muw_internal.hpp"
 
@@ -190,7 +192,8 @@ muw_status dispatch_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t 
 
 size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M)
 {
-    if (d.wdtype == MUW_BF16 && M >= 1 && M <= 16) return stream_gemm_workspace_bytes(L, M, 1);
+    if (d.wdtype == MUW_BF16 && M >= 1 && M <= 16)  // (streaming kernel, or the tile kernels if a tile stream is too long for it)
+        return std::max(stream_gemm_workspace_bytes(L, M, 1), tile_gemm_workspace_bytes(L, M));
     if (d.wdtype == MUW_BF16 && M > 16) return tile_gemm_workspace_bytes(L, M);
     return 0;
 }

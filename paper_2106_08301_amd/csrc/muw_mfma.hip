@@ -302,7 +302,8 @@ int tile_splits(const Layout &L, int64_t M, int64_t tm = 128, bool pipelined = f
     const int64_t wgs = ((L.N + kTN - 1) / kTN) * ((M + tm - 1) / tm);
     const int64_t resident = int64_t(tile_cus()) * (tm >= 256 ? 1 : 2);
     if (wgs > resident / (pipelined ? 4 : 2) || L.KT < 2) return 1;
-    int64_t s = (resident + wgs - 1) / wgs;
+    // (the pipelined kernel's workgroups fill the chip exactly: one more than fits costs a whole second round)
+    int64_t s = pipelined ? resident / wgs : (resident + wgs - 1) / wgs;
     if (s > L.KT) s = L.KT;
     if (s > 16) s = 16;
     return int(s);
@@ -342,7 +343,8 @@ muw_status launch_tile_b(TileGemmArgs a, const Layout &L, void *ws, size_t ws_by
 
 bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 {
-    if (d.wdtype != MUW_BF16 || a.blobs || a.M <= 16) return false;
+    // (M <= 16 normally goes to the streaming kernel; it comes here when a tile stream exceeds that kernel's ring slots)
+    if (d.wdtype != MUW_BF16 || a.blobs || a.M < 1) return false;
     if (L.K % 8 != 0 || a.ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(a.X) & 15u)) return false;
     if ((a.M + 127) / 128 > 65535) return false;
     return true;

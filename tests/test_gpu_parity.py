@@ -215,6 +215,17 @@ def test_small_m_kernel_for_block_length_16(muw, oracle, M, N, K, r_u, r_p, span
     check_close(to_f64(muw.muw_gemm(layer, to_device(X))), oracle.gemm(X.f64(), What))
 
 
+def test_small_m_with_tile_streams_beyond_the_streaming_kernel(muw, oracle):
+    # a third of the blocks dense: tile streams of more than 2 KiB do not fit the streaming kernel's LDS
+    # ring, and M <= 16 runs through the tile kernels instead
+    case = synth.LinearCase("t", 9, 80, 1024, 8, 0.1, 0.55, "bf16", 0.02, 777)
+    X, W = synth.make_linear(case)
+    (_, _, _, What), _ = oracle_encode(oracle, W, 8, 0.1, 0.55)
+    layer = muw.muw_encode(to_device(W), 8, 0.1, 0.55)
+    assert layer.desc.max_tile_bytes > 2048
+    check_close(to_f64(muw.muw_gemm(layer, to_device(X))), oracle.gemm(X.f64(), What))
+
+
 def test_small_m_kernel_long_walk_over_several_matrices(muw, oracle):
     # 24 matrices x 688 strips = 16512 strips: each of the 256 workgroups walks 64 or 65 strips, across
     # matrix boundaries and past the 64 entries its directory window holds at a time
