@@ -414,114 +414,141 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     // One 64-k step kp with weight buffer and payload set PAR = kp % 2.  STEADY: at least three more
     // steps follow, so every prefetch of the step happens (known at compile time: a loaded value that
     // merges with an old one at the end of a branch is copied there, and the copy waits for the load).
-    auto step = [&](int kp, auto par, auto steady) {
+    // MFMA_FIRST: the wave runs its MFMAs before its prefetch and decode work instead of after.  The two
+    // waves of a SIMD (w and w + 4) take opposite orders, so that between two barriers one of them feeds
+    // the matrix pipe while the other one issues loads and decodes -- in the same order they would both
+    // do the same thing at the same time, and the pipe would idle half of the step.
+    auto step = [&](int kp, auto par, auto steady, auto mfma_first) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par)::value;
         constexpr bool STEADY = decltype(steady)::value;
+        constexpr bool MFMA_FIRST = decltype(mfma_first)::value;
         const bool full = STEADY || kp + 2 < kp_hi, more = STEADY || kp + 1 < kp_hi;
         PanelMasks<B> mf[NS], md[NS];
         constexpr int AHEAD = NAB - 1;  // steps the activation DMA runs ahead
         const int abuf_dma = abuf + AHEAD >= NAB ? abuf + AHEAD - NAB : abuf + AHEAD;
-        if constexpr (STEADY) {
-            issue_a(kp + AHEAD, abuf_dma);
-            const int pk = kp + 4 < kp_hi ? kp + 4 : kp + 2;  // (past the K range: any valid panel, never used)
-#pragma unroll
-            for (int j = 0; j < NS; ++j)
-                issue_mask_dma<B>(peek_tile(j, pk), pk % kTilePanels, lane, M_lds[wave][(kp + 4) % NMS][j]);
-            // masks of the panels fetched and decoded in this step (requested two and three steps ago)
-            uint32_t rf[NS], rdm[NS];
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
-                rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % NMS][j], lane);
-            }
-            if constexpr (NS == 2)
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]), "+v"(rdm[0]), "+v"(rdm[NS - 1]));
-            else
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rdm[0]));
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                masks_from_lanes<B>(rf[j], mf[j]);
-                masks_from_lanes<B>(rdm[j], md[j]);
-            }
-            fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2
-            open_tiles(kp + 3, false);
-        } else {
-            // tail (and short K ranges): scalar mask loads, waited for on the spot
-            if (kp + AHEAD < kp_hi) issue_a(kp + AHEAD, abuf_dma);
-            if (full) {
-#pragma unroll
-                for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
-                fetch(mf, pay[PAR], ptile[PAR]);
-            }
-            if (kp + 3 < kp_hi) open_tiles(kp + 3, false);
-            if (more) {
+        const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
+        u32x4_t bf[4][2];
+        u32x4_t af[2][2];
+
+        // ---- prefetches: activation tile, masks, payload, directory entries
+        auto prefetch = [&]() __attribute__((always_inline)) {
+            if constexpr (STEADY) {
+                issue_a(kp + AHEAD, abuf_dma);
+                const int pk = kp + 4 < kp_hi ? kp + 4 : kp + 2;  // (past the K range: any valid panel, never used)
 #pragma unroll
                 for (int j = 0; j < NS; ++j)
-                    if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
-            }
-        }
-        TPROF_MARK(0);  // DMA, payload and mask loads issued
-        const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
-        // B fragments of this step (8 reads), first A fragments
-        u32x4_t bf[4][2];
+                    issue_mask_dma<B>(peek_tile(j, pk), pk % kTilePanels, lane, M_lds[wave][(kp + 4) % NMS][j]);
+                // masks of the panels fetched and decoded in this step (requested two and three steps ago)
+                uint32_t rf[NS], rdm[NS];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bf[0][h] = lds_read_b128_at<PAR * BBYTES + 0 * 2048>(baddr[h]);
-            bf[1][h] = lds_read_b128_at<PAR * BBYTES + 1 * 2048>(baddr[h]);
-            bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
-            bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
-        }
-        u32x4_t af[2][2];
-        af[0][0] = lds_read_b128_at<0>(a0);
-        af[0][1] = lds_read_b128_at<0>(a1);
-        asm volatile("s_waitcnt lgkmcnt(2)"
-                     : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
-                       "+v"(bf[2][1]), "+v"(bf[3][1]));
-        TPROF_MARK(1);  // B fragment reads
-        if (more) {
-            // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
-            // at least the activation and mask DMA and the payload loads of this step.
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                if (STEADY)
-                    wait_payload<NA + NS + NS * kPayloadLoads<B>>(pay[PAR ^ 1][j]);
+                for (int j = 0; j < NS; ++j) {
+                    rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
+                    rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % NMS][j], lane);
+                }
+                if constexpr (NS == 2)
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]), "+v"(rdm[0]), "+v"(rdm[NS - 1]));
                 else
-                    wait_payload<0>(pay[PAR ^ 1][j]);
-            }
-            decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
-        }
-        TPROF_MARK(2);  // decode (waits for the payload) and LDS writes
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rdm[0]));
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int c = mb & 1;
-            if (mb + 1 < MB) {
-                // (the offset is an immediate of the instruction: spell the cases out)
-                auto rd = [&](auto mbc) {
-                    constexpr int OFF = decltype(mbc)::value * 2048;
-                    af[c ^ 1][0] = lds_read_b128_at<OFF>(a0);
-                    af[c ^ 1][1] = lds_read_b128_at<OFF>(a1);
-                };
-                if (mb == 0) rd(std::integral_constant<int, 1>{});
-                if (mb == 1) rd(std::integral_constant<int, 2>{});
-                if (mb == 2) rd(std::integral_constant<int, 3>{});
-                if (mb == 3) rd(std::integral_constant<int, 4 % MB>{});
-                if (mb == 4) rd(std::integral_constant<int, 5 % MB>{});
-                if (mb == 5) rd(std::integral_constant<int, 6 % MB>{});
-                if (mb == 6) rd(std::integral_constant<int, 7 % MB>{});
-                asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                for (int j = 0; j < NS; ++j) {
+                    masks_from_lanes<B>(rf[j], mf[j]);
+                    masks_from_lanes<B>(rdm[j], md[j]);
+                }
+                fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2
+                open_tiles(kp + 3, false);
             } else {
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                // tail (and short K ranges): scalar mask loads, waited for on the spot
+                if (kp + AHEAD < kp_hi) issue_a(kp + AHEAD, abuf_dma);
+                if (full) {
+#pragma unroll
+                    for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
+                    fetch(mf, pay[PAR], ptile[PAR]);
+                }
+                if (kp + 3 < kp_hi) open_tiles(kp + 3, false);
+                if (more) {
+#pragma unroll
+                    for (int j = 0; j < NS; ++j)
+                        if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
+                }
             }
+            TPROF_MARK(0);  // DMA, payload and mask loads issued
+        };
+        // ---- B fragments of this step (8 reads), first A fragments
+        auto read_fragments = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < 2; ++h) {
+                bf[0][h] = lds_read_b128_at<PAR * BBYTES + 0 * 2048>(baddr[h]);
+                bf[1][h] = lds_read_b128_at<PAR * BBYTES + 1 * 2048>(baddr[h]);
+                bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
+                bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
+            }
+            af[0][0] = lds_read_b128_at<0>(a0);
+            af[0][1] = lds_read_b128_at<0>(a1);
+            asm volatile("s_waitcnt lgkmcnt(2)"
+                         : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
+                           "+v"(bf[2][1]), "+v"(bf[3][1]));
+            TPROF_MARK(1);  // B fragment reads
+        };
+        // ---- decode of the next step's weights into the other buffer
+        auto decode_next = [&]() __attribute__((always_inline)) {
+            if (more) {
+                // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
+                // at least the activation and mask DMA and the payload loads of this step.
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc[mb][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[c][h]),
-                                                                         __builtin_bit_cast(bf16x8, bf[s][h]),
-                                                                         acc[mb][s], 0, 0, 0);
+                for (int j = 0; j < NS; ++j) {
+                    if (STEADY)
+                        wait_payload<NA + NS + NS * kPayloadLoads<B>>(pay[PAR ^ 1][j]);
+                    else
+                        wait_payload<0>(pay[PAR ^ 1][j]);
+                }
+                decode_to_lds(md, pay[PAR ^ 1], ptile[PAR ^ 1], PAR ^ 1);
+            }
+            TPROF_MARK(2);  // decode (waits for the payload) and LDS writes
+        };
+        auto mfma_loop = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int c = mb & 1;
+                if (mb + 1 < MB) {
+                    // (the offset is an immediate of the instruction: spell the cases out)
+                    auto rd = [&](auto mbc) {
+                        constexpr int OFF = decltype(mbc)::value * 2048;
+                        af[c ^ 1][0] = lds_read_b128_at<OFF>(a0);
+                        af[c ^ 1][1] = lds_read_b128_at<OFF>(a1);
+                    };
+                    if (mb == 0) rd(std::integral_constant<int, 1>{});
+                    if (mb == 1) rd(std::integral_constant<int, 2>{});
+                    if (mb == 2) rd(std::integral_constant<int, 3>{});
+                    if (mb == 3) rd(std::integral_constant<int, 4 % MB>{});
+                    if (mb == 4) rd(std::integral_constant<int, 5 % MB>{});
+                    if (mb == 5) rd(std::integral_constant<int, 6 % MB>{});
+                    if (mb == 6) rd(std::integral_constant<int, 7 % MB>{});
+                    asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        acc[mb][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[c][h]),
+                                                                             __builtin_bit_cast(bf16x8, bf[s][h]),
+                                                                             acc[mb][s], 0, 0, 0);
+            }
+            TPROF_MARK(3);  // MFMA loop
+        };
+        if constexpr (MFMA_FIRST) {
+            read_fragments();
+            mfma_loop();
+            prefetch();
+            decode_next();
+        } else {
+            prefetch();
+            read_fragments();
+            decode_next();
+            mfma_loop();
         }
         abuf = abuf + 1 == NAB ? 0 : abuf + 1;
-        TPROF_MARK(3);  // MFMA loop
         end_of_step(STEADY);
         TPROF_MARK(4);  // end-of-step waits and barrier
     };
@@ -552,16 +579,23 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             decode_to_lds(m0, pay[0], ptile[0], 0);
         }
         end_of_step(false);
-        int kp = kp_lo;
-        for (; kp + 4 < kp_hi; kp += 2) {
-            step(kp, std::integral_constant<int, 0>{}, std::true_type{});
-            step(kp + 1, std::integral_constant<int, 1>{}, std::true_type{});
-        }
-        for (; kp + 1 < kp_hi; kp += 2) {
-            step(kp, std::integral_constant<int, 0>{}, std::false_type{});
-            step(kp + 1, std::integral_constant<int, 1>{}, std::false_type{});
-        }
-        if (kp < kp_hi) step(kp, std::integral_constant<int, 0>{}, std::false_type{});
+        auto k_loop = [&](auto mfma_first) __attribute__((always_inline)) {
+            int kp = kp_lo;
+            for (; kp + 4 < kp_hi; kp += 2) {
+                step(kp, std::integral_constant<int, 0>{}, std::true_type{}, mfma_first);
+                step(kp + 1, std::integral_constant<int, 1>{}, std::true_type{}, mfma_first);
+            }
+            for (; kp + 1 < kp_hi; kp += 2) {
+                step(kp, std::integral_constant<int, 0>{}, std::false_type{}, mfma_first);
+                step(kp + 1, std::integral_constant<int, 1>{}, std::false_type{}, mfma_first);
+            }
+            if (kp < kp_hi) step(kp, std::integral_constant<int, 0>{}, std::false_type{}, mfma_first);
+        };
+        // (every wave runs the same number of steps, hence of barriers, in either order)
+        if (NW == 8 && wave >= NW / 2)
+            k_loop(std::true_type{});
+        else
+            k_loop(std::false_type{});
     }
 #ifdef MUW_PROFILE_TILE
     if (lane == 0)
