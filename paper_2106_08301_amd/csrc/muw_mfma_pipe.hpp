@@ -603,26 +603,38 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 #endif
 
     // ---- epilogue: lane holds Y[m = 4 g + v][n = r] of each 16 x 16 block
+    const bool nchw = a.pix && !a.Ypart;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb) {
+        const int64_t mq = m0 + wm * 64 + mb * 16 + 4 * g;  // the lane's 4 consecutive rows
+        // NCHW: image and pixel of row mq (one 32-bit division per 16-row block; M < 2^30)
+        uint32_t img = 0, px = 0;
+        if (nchw) {
+            img = uint32_t(mq) / uint32_t(a.pix);
+            px = uint32_t(mq) - img * uint32_t(a.pix);
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int64_t n = n0 + wn * 64 + s * 16 + r;
             if (n >= L.N) continue;
-            const int64_t mq = m0 + wm * 64 + mb * 16 + 4 * g;
-            if (a.pix && !a.Ypart) {
-                // NCHW: for a fixed output channel the lane's 4 rows are 4 consecutive pixels
+            if (nchw) {
+                // for a fixed output channel the lane's 4 rows are 4 consecutive pixels (of one image if
+                // the pixel count is a multiple of 4)
                 const int64_t pix = a.pix;
                 if ((pix & 3) == 0 && mq + 3 < a.M && a.ydtype == MUW_F32) {
-                    const int64_t b = mq / pix, pp = mq % pix;
-                    *reinterpret_cast<f32x4 *>(static_cast<float *>(a.Y) + (b * L.N + n) * pix + pp) = acc[mb][s];
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(a.Y) + (int64_t(img) * L.N + n) * pix + px) = acc[mb][s];
                     continue;
                 }
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int64_t m = mq + v;
-                    if (m >= a.M) continue;
-                    const int64_t idx = ((m / pix) * L.N + n) * pix + m % pix;
+                    if (mq + v >= a.M) continue;
+                    const bool next = px + uint32_t(v) >= uint32_t(pix);  // (rows past the end of this image: divide again)
+                    uint32_t bi = img, pi = px + uint32_t(v);
+                    if (next) {
+                        bi = uint32_t(mq + v) / uint32_t(pix);
+                        pi = uint32_t(mq + v) - bi * uint32_t(pix);
+                    }
+                    const int64_t idx = (int64_t(bi) * L.N + n) * pix + pi;
                     if (a.ydtype == MUW_F32)
                         static_cast<float *>(a.Y)[idx] = acc[mb][s][v];
                     else
@@ -642,6 +654,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                     static_cast<uint16_t *>(a.Y)[m * a.ldy + n] = f32_to_bf16_rne(acc[mb][s][v]);
             }
         }
+    }
 }
 
 // The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels.
