@@ -370,6 +370,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         for (int s = 0; s < 4; ++s) acc[mb][s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     Payload<B> pay[2][NS];  // [step parity][strip]
+    PanelMasks<B> mset[2][NS];  // [step parity][strip]: masks the step fetched its payload with
     // tile stream of panel kp while the cursor is still in the tile of panel kp - 2
     auto peek_tile = [&](int j, int kp) -> uint64_t {
         return kp / kTilePanels != (kp - 2) / kTilePanels ? tile_address(cur[j].next_off16) : cur[j].tile;
@@ -423,7 +424,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         constexpr bool STEADY = decltype(steady)::value;
         constexpr bool MFMA_FIRST = decltype(mfma_first)::value;
         const bool full = STEADY || kp + 2 < kp_hi, more = STEADY || kp + 1 < kp_hi;
-        PanelMasks<B> mf[NS], md[NS];
+        // masks of the panel whose payload is fetched in this step (kp + 2) and of the one decoded in it
+        // (kp + 1: the set the previous step fetched with)
+        PanelMasks<B>(&mf)[NS] = mset[PAR];
+        PanelMasks<B>(&md)[NS] = mset[PAR ^ 1];
         constexpr int AHEAD = NAB - 1;  // steps the activation DMA runs ahead
         const int abuf_dma = abuf + AHEAD >= NAB ? abuf + AHEAD - NAB : abuf + AHEAD;
         const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
@@ -438,22 +442,16 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 #pragma unroll
                 for (int j = 0; j < NS; ++j)
                     issue_mask_dma<B>(peek_tile(j, pk), pk % kTilePanels, lane, M_lds[wave][(kp + 4) % NMS][j]);
-                // masks of the panels fetched and decoded in this step (requested two and three steps ago)
-                uint32_t rf[NS], rdm[NS];
+                // masks of the panel fetched in this step (requested two steps ago)
+                uint32_t rf[NS];
 #pragma unroll
-                for (int j = 0; j < NS; ++j) {
-                    rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
-                    rdm[j] = read_mask_lanes<B>(M_lds[wave][(kp + 1) % NMS][j], lane);
-                }
+                for (int j = 0; j < NS; ++j) rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
                 if constexpr (NS == 2)
-                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]), "+v"(rdm[0]), "+v"(rdm[NS - 1]));
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]));
                 else
-                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rdm[0]));
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]));
 #pragma unroll
-                for (int j = 0; j < NS; ++j) {
-                    masks_from_lanes<B>(rf[j], mf[j]);
-                    masks_from_lanes<B>(rdm[j], md[j]);
-                }
+                for (int j = 0; j < NS; ++j) masks_from_lanes<B>(rf[j], mf[j]);
                 fetch(mf, pay[PAR], ptile[PAR]);  // payload of step kp + 2
                 open_tiles(kp + 3, false);
             } else {
@@ -555,7 +553,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 
     if (kp_lo < kp_hi) {
         {  // (kp_lo is the first panel of a tile: splits cover whole tiles)
-            PanelMasks<B> m0[NS], m1[NS];
+            PanelMasks<B> m0[NS];
+            PanelMasks<B>(&m1)[NS] = mset[1];  // (kp_lo is even: the first step decodes with the set of parity 1)
             open_tiles(kp_lo, true);
             issue_a(kp_lo, 0);
             if (NAB == 3 && kp_lo + 1 < kp_hi) issue_a(kp_lo + 1, 1);
