@@ -357,9 +357,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         cur[j].ru = cur[j].rd = 0;
     };
     auto open_tiles = [&](int kp, bool first) {
-        if (kp % kTilePanels == 0) {
+        if ((uint32_t(kp) & (kTilePanels - 1)) == 0) {  // (panel indices are never negative: unsigned arithmetic is one instruction)
 #pragma unroll
-            for (int j = 0; j < NS; ++j) open_tile(j, kp / kTilePanels, first);
+            for (int j = 0; j < NS; ++j) open_tile(j, int(uint32_t(kp) / kTilePanels), first);
         }
     };
 
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     PanelMasks<B> mset[2][NS];  // [step parity][strip]: masks the step fetched its payload with
     // tile stream of panel kp while the cursor is still in the tile of panel kp - 2
     auto peek_tile = [&](int j, int kp) -> uint64_t {
-        return kp / kTilePanels != (kp - 2) / kTilePanels ? tile_address(cur[j].next_off16) : cur[j].tile;
+        return uint32_t(kp) / kTilePanels != uint32_t(kp - 2) / kTilePanels ? tile_address(cur[j].next_off16) : cur[j].tile;
     };
     auto fetch = [&](const PanelMasks<B> (&m)[NS], Payload<B> (&dst)[NS], uint64_t (&dst_tile)[NS]) {
 #pragma unroll
@@ -441,11 +441,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 const int pk = kp + 4 < kp_hi ? kp + 4 : kp + 2;  // (past the K range: any valid panel, never used)
 #pragma unroll
                 for (int j = 0; j < NS; ++j)
-                    issue_mask_dma<B>(peek_tile(j, pk), pk % kTilePanels, lane, M_lds[wave][(kp + 4) % NMS][j]);
+                    issue_mask_dma<B>(peek_tile(j, pk), int(uint32_t(pk) % kTilePanels), lane, M_lds[wave][uint32_t(kp + 4) % NMS][j]);
                 // masks of the panel fetched in this step (requested two steps ago)
                 uint32_t rf[NS];
 #pragma unroll
-                for (int j = 0; j < NS; ++j) rf[j] = read_mask_lanes<B>(M_lds[wave][(kp + 2) % NMS][j], lane);
+                for (int j = 0; j < NS; ++j) rf[j] = read_mask_lanes<B>(M_lds[wave][uint32_t(kp + 2) % NMS][j], lane);
                 if constexpr (NS == 2)
                     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(rf[0]), "+v"(rf[NS - 1]));
                 else
@@ -459,14 +459,14 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 if (kp + AHEAD < kp_hi) issue_a(kp + AHEAD, abuf_dma);
                 if (full) {
 #pragma unroll
-                    for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, (kp + 2) % kTilePanels, mf[j]);
+                    for (int j = 0; j < NS; ++j) load_panel_masks<B>(cur[j].tile, int(uint32_t(kp + 2) % kTilePanels), mf[j]);
                     fetch(mf, pay[PAR], ptile[PAR]);
                 }
                 if (kp + 3 < kp_hi) open_tiles(kp + 3, false);
                 if (more) {
 #pragma unroll
                     for (int j = 0; j < NS; ++j)
-                        if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], (kp + 1) % kTilePanels, md[j]);
+                        if (ptile[PAR ^ 1][j]) load_panel_masks<B>(ptile[PAR ^ 1][j], int(uint32_t(kp + 1) % kTilePanels), md[j]);
                 }
             }
             TPROF_MARK(0);  // DMA, payload and mask loads issued
@@ -571,7 +571,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 for (int j = 0; j < NS; ++j)
 #pragma unroll
                     for (int pp = 1; pp <= 3; ++pp)
-                        issue_mask_dma<B>(cur[j].tile, pp, lane, M_lds[wave][(kp_lo + pp) % NMS][j]);
+                        issue_mask_dma<B>(cur[j].tile, pp, lane, M_lds[wave][uint32_t(kp_lo + pp) % NMS][j]);
             }
 #pragma unroll
             for (int j = 0; j < NS; ++j) wait_payload<0>(pay[0][j]);
