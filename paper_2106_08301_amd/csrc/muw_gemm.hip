@@ -192,9 +192,9 @@ muw_status dispatch_wave_gemm(const muw_desc &d, const Layout &L, const uint8_t 
 
 size_t gemm_workspace_bytes(const muw_desc &d, const Layout &L, int64_t M)
 {
-    if (d.wdtype == MUW_BF16 && M >= 1 && M <= 16)  // (streaming kernel, or the tile kernels if a tile stream is too long for it)
+    // (small M: the streaming kernel, or the tile kernels if a tile stream is too long for it)
+    if (d.wdtype == MUW_BF16 && M >= 1)
         return std::max(stream_gemm_workspace_bytes(L, M, 1), tile_gemm_workspace_bytes(L, M));
-    if (d.wdtype == MUW_BF16 && M > 16) return tile_gemm_workspace_bytes(L, M);
     return 0;
 }
 

@@ -40,6 +40,9 @@ typedef __attribute__((address_space(1))) uint16_t g_u16;
 typedef const __attribute__((address_space(4))) uint64_t c_u64;
 
 constexpr int kWaves = 16;       // wavefronts per workgroup = tile columns handled at once
+// Up to this many activation rows the streaming kernels run, one pass over the weights (blockIdx.z) per 16
+// rows; beyond it the MFMA tile kernels are faster.
+constexpr int kStreamMaxM = 48;
 constexpr int kP = kTilePanels;  // panels per tile (4)
 static_assert(kP == 4, "the streaming kernel is written for 4-panel tiles");
 
@@ -286,6 +289,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream_bf16(StreamArgs a, Strea
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63, r = lane & 15, g4 = lane >> 4;
     const int chunk = blockIdx.y;
+    const int m_first = 16 * int(blockIdx.z);  // more than 16 activation rows: one pass over the weights per 16
     const int kt = chunk * kWaves + wave;
     const bool active = kt < L.KT;
 
@@ -379,8 +383,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream_bf16(StreamArgs a, Strea
                 for (int h = 0; h < 2; ++h) {
                     const int k = kt * kTileK + p * kPanelK + 16 * g4 + 8 * h;
                     uint4 v = make_uint4(0, 0, 0, 0);
-                    if (r < a.M && k + 8 <= L.K) {
-                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
+                    if (m_first + r < a.M && k + 8 <= L.K) {
+                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t((m_first + r) * ldx + k) * 2u));
                         v = make_uint4(t.x, t.y, t.z, t.w);
                     }
                     xr[p][h] = v;
@@ -437,7 +441,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream_bf16(StreamArgs a, Strea
                                     uint64_t(int64_t(chunk) * a.G + gi) * uint64_t(a.M) * uint64_t(L.N) * 4u;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int m = 4 * g4 + v;
+                    const int m = m_first + 4 * g4 + v;
                     if (m >= a.M) continue;
                     if (a.Ypart)
                         *(g_float *)(Yp + uint64_t(uint32_t(m * ncols + n) * 4u)) = t[v];
@@ -493,7 +497,7 @@ muw_status launch_stream_variant(StreamArgs a, const Layout &L, hipStream_t st)
     int grid = a.nstrips < cus ? a.nstrips : cus;
     a.per_wg = (a.nstrips + grid - 1) / grid;
     grid = (a.nstrips + a.per_wg - 1) / a.per_wg;
-    dim3 g(unsigned(grid), unsigned(a.nchunk), 1);
+    dim3 g(unsigned(grid), unsigned(a.nchunk), unsigned((a.M + 15) / 16));
     k_stream_bf16<B, NCH, D><<<g, kWaves * 64, 0, st>>>(a, geom);
     return hip_status(hipGetLastError());
 }
@@ -517,7 +521,7 @@ muw_status launch_stream_b(StreamArgs a, const Layout &L, int nch, hipStream_t s
 // streams that fit the LDS ring.)
 bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 {
-    if (d.wdtype != MUW_BF16 || a.M > 16 || a.M < 1) return false;
+    if (d.wdtype != MUW_BF16 || a.M > kStreamMaxM || a.M < 1) return false;
     if (d.max_tile_bytes <= 0 || d.max_tile_bytes > 2048) return false;
     if (L.K % 8 != 0 || a.ldx % 8 != 0) return false;
     if (a.ldx >= (1 << 26) || a.ldy >= (1 << 26) || L.N >= (1 << 26)) return false;  // 32-bit offsets in the kernel
@@ -529,6 +533,7 @@ bool stream_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &
 size_t stream_gemm_workspace_bytes(const Layout &L, int64_t M, int G)
 {
     const int64_t nchunk = (L.KT + kWaves - 1) / kWaves;
+    if (M > kStreamMaxM) return 0;  // (not this kernel's problem)
     return nchunk > 1 ? size_t(nchunk) * size_t(G) * size_t(M) * size_t(L.N) * sizeof(float) : 0;
 }
 

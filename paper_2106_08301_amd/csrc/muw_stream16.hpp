@@ -205,6 +205,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream16_bf16(Stream16Args)
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63, r = lane & 15, g4 = lane >> 4;
     const int chunk = blockIdx.y;
+    const int m_first = 16 * int(blockIdx.z);  // more than 16 activation rows: one pass over the weights per 16
     const int kt = chunk * kWaves + wave;
     const int KT = MUW_KARG(int32_t, KT), NS = MUW_KARG(int32_t, NS);
     const bool active = kt < KT;
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream16_bf16(Stream16Args)
                                 uint64_t(int64_t(chunk) * o.G + gi_s) * uint64_t(o.M) * uint64_t(o.N) * 4u;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int m = 4 * g4 + v;
+                const int m = m_first + 4 * g4 + v;  // (this workgroup's 16 activation rows)
                 if (m >= o.M) continue;
                 if (o.Ypart)
                     *(g_float *)(Yp + uint64_t(uint32_t(m * o.N + n) * 4u)) = t[v];
@@ -370,8 +371,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream16_bf16(Stream16Args)
                 for (int h = 0; h < 2; ++h) {
                     const int k = kt * kTileK + p * kPanelK + 16 * g4 + 8 * h;
                     uint4 v = make_uint4(0, 0, 0, 0);
-                    if (r < M && k + 8 <= K) {
-                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t(r * ldx + k) * 2u));
+                    if (m_first + r < M && k + 8 <= K) {
+                        const u32x4_t t = *(g_cu32x4 *)(X + uint64_t(uint32_t((m_first + r) * ldx + k) * 2u));
                         v = make_uint4(t.x, t.y, t.z, t.w);
                     }
                     xr[p][h] = v;
@@ -485,7 +486,7 @@ muw_status launch_stream16_variant(StreamArgs a, const Layout &L, hipStream_t st
     int grid = k.nstrips < cus ? k.nstrips : cus;
     k.per_wg = (k.nstrips + grid - 1) / grid;
     grid = (k.nstrips + k.per_wg - 1) / k.per_wg;
-    dim3 g(unsigned(grid), unsigned(a.nchunk), 1);
+    dim3 g(unsigned(grid), unsigned(a.nchunk), unsigned((a.M + 15) / 16));
     k_stream16_bf16<SLOT256, D, R, LAG><<<g, kWaves * 64, 0, st>>>(k);
     return hip_status(hipGetLastError());
 }

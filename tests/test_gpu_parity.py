@@ -215,6 +215,17 @@ def test_small_m_kernel_for_block_length_16(muw, oracle, M, N, K, r_u, r_p, span
     check_close(to_f64(muw.muw_gemm(layer, to_device(X))), oracle.gemm(X.f64(), What))
 
 
+@pytest.mark.parametrize("M,N,K,B", [(17, 40, 512, 16), (48, 72, 1024, 8), (33, 24, 4352, 16), (40, 56, 8192, 8)])
+def test_streaming_kernels_in_blocks_of_16_rows(muw, oracle, M, N, K, B):
+    # 16 < M <= 48 stays on the streaming kernels: one pass over the weights per 16 activation rows
+    case = synth.LinearCase("t", M, N, K, B, 0.6, 0.35, "bf16", 0.02, 880 + M)
+    X, W = synth.make_linear(case)
+    (_, _, _, What), _ = oracle_encode(oracle, W, B, 0.6, 0.35)
+    layer = muw.muw_encode(to_device(W), B, 0.6, 0.35)
+    assert layer.desc.max_tile_bytes <= 2048
+    check_close(to_f64(muw.muw_gemm(layer, to_device(X))), oracle.gemm(X.f64(), What))
+
+
 def test_small_m_with_tile_streams_beyond_the_streaming_kernel(muw, oracle):
     # a third of the blocks dense: tile streams of more than 2 KiB do not fit the streaming kernel's LDS
     # ring, and M <= 16 runs through the tile kernels instead
