@@ -26,7 +26,9 @@
  * Sec. 4.5, closed-form Gaussian statistics, dense/all-pruned special cases of the GEMM, im2col and
  * library convolution for the conv; for the ADMM steps the unconstrained and the feasible special
  * cases, the dual variable as the running sum of residuals, finite differences of the penalty, and
- * the brute-force projection again.  No function in this file is "parity unpinned".
+ * the brute-force projection again; for the two-dimensional block shapes the [B,1] special case, the
+ * brute-force projection and selection on [2,2] blocks, Table 1's [2,2] row and a planted rectangle.
+ * No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -229,6 +231,116 @@ done:
     free(e_u);
     free(order);
     return rc;
+}
+
+/* ---- Two-dimensional block shapes [BK, BN] (Sec. 3.2, Table 1: the first extent lies along the
+ * contraction direction, the one whose multiplications a unified block shares; the second along the
+ * output rows).  Block j = (n / BN) * (K / BK) + kb holds W[n0 + r][kb*BK + l], r < BN, l < BK, visited
+ * row by row (r outer, l inner): that is the "left to right" of the sums below.  Everything else is the
+ * definition used for [B,1] blocks above: q = mean |w| over the whole block (Eq. 2), e_p and e_u the
+ * squared distances to the all-zero and to the unified block (Eq. 6), pruning decided first. */
+int oracle_block_scores_2d(const double *Wg, int64_t N, int64_t K, int64_t BK, int64_t BN, double *q_out,
+                           double *e_p_out, double *e_u_out)
+{
+    int64_t KB = K / BK, NS = N / BN;
+    for (int64_t s = 0; s < NS; ++s)
+        for (int64_t kb = 0; kb < KB; ++kb) {
+            double s1 = 0.0, e_p = 0.0, e_u = 0.0;
+            for (int64_t r = 0; r < BN; ++r)
+                for (int64_t l = 0; l < BK; ++l) {
+                    double w = Wg[(s * BN + r) * K + kb * BK + l];
+                    if (!isfinite(w)) return -2;
+                    s1 = s1 + fabs(w);
+                }
+            double q = s1 / (double)(BK * BN);
+            for (int64_t r = 0; r < BN; ++r)
+                for (int64_t l = 0; l < BK; ++l) {
+                    double w = Wg[(s * BN + r) * K + kb * BK + l];
+                    double sq = w * w;
+                    e_p = e_p + sq;
+                }
+            for (int64_t r = 0; r < BN; ++r)
+                for (int64_t l = 0; l < BK; ++l) {
+                    double d = fabs(Wg[(s * BN + r) * K + kb * BK + l]) - q;
+                    double dd = d * d;
+                    e_u = e_u + dd;
+                }
+            int64_t j = s * KB + kb;
+            q_out[j] = q;
+            e_p_out[j] = e_p;
+            e_u_out[j] = e_u;
+        }
+    return 0;
+}
+
+/* Unify() for [BK, BN] blocks: tags[NB] and mags[NB] (NB = (N/BN)*(K/BK)) and the projected weights
+ * What[N][K]; the sign of every unified weight is the sign of What (Eq. 2: w >= 0 maps to +q^).
+ * Returns 0; -1 bad arguments; -2 non-finite weight. */
+int oracle_encode_2d(const double *Wg, int64_t N, int64_t K, int64_t BK, int64_t BN, int64_t n_u,
+                     int64_t n_p, int storage, uint8_t *tags, double *mags, double *What)
+{
+    if (N <= 0 || K <= 0 || BK <= 0 || BN <= 0 || K % BK != 0 || N % BN != 0) return -1;
+    int64_t KB = K / BK, NB = (N / BN) * KB;
+    if (n_p < 0 || n_u < 0 || n_p + n_u > NB) return -1;
+
+    double *q = (double *)malloc(sizeof(double) * (size_t)NB);
+    double *e_p = (double *)malloc(sizeof(double) * (size_t)NB);
+    double *e_u = (double *)malloc(sizeof(double) * (size_t)NB);
+    oracle_keyed *order = (oracle_keyed *)malloc(sizeof(oracle_keyed) * (size_t)NB);
+    int rc = oracle_block_scores_2d(Wg, N, K, BK, BN, q, e_p, e_u);
+    if (rc != 0) goto done;
+
+    for (int64_t j = 0; j < NB; ++j) {
+        tags[j] = ORACLE_TAG_DENSE;
+        order[j].key = e_p[j];
+        order[j].idx = j;
+    }
+    qsort(order, (size_t)NB, sizeof(oracle_keyed), oracle_keyed_cmp);
+    for (int64_t r = 0; r < n_p; ++r) tags[order[r].idx] = ORACLE_TAG_PRUNED;
+
+    int64_t rest = 0;
+    for (int64_t j = 0; j < NB; ++j)
+        if (tags[j] != ORACLE_TAG_PRUNED) {
+            order[rest].key = e_u[j];
+            order[rest].idx = j;
+            ++rest;
+        }
+    qsort(order, (size_t)rest, sizeof(oracle_keyed), oracle_keyed_cmp);
+    for (int64_t r = 0; r < n_u; ++r) tags[order[r].idx] = ORACLE_TAG_UNIFIED;
+
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t j = (n / BN) * KB + k / BK;
+            double w = Wg[n * K + k];
+            if (tags[j] == ORACLE_TAG_PRUNED) {
+                What[n * K + k] = 0.0;
+            } else if (tags[j] == ORACLE_TAG_UNIFIED) {
+                double qh = oracle_round_to_storage(q[j], storage);
+                What[n * K + k] = (w >= 0.0) ? qh : -qh;
+            } else {
+                What[n * K + k] = w;
+            }
+        }
+    for (int64_t j = 0; j < NB; ++j)
+        mags[j] = (tags[j] == ORACLE_TAG_UNIFIED) ? oracle_round_to_storage(q[j], storage) : 0.0;
+done:
+    free(q);
+    free(e_p);
+    free(e_u);
+    free(order);
+    return rc;
+}
+
+/* Table 1 for a [BK, BN] block: a unified block stores one value and needs one multiplication per output
+ * row it spans (BN), a dense block BK*BN of each; the exact format adds a 2-bit tag per block and one sign
+ * bit per unified weight. */
+void oracle_counters_2d(int64_t NB, int64_t BK, int64_t BN, int64_t n_u, int64_t n_p, int64_t value_bits,
+                        int64_t *params, int64_t *mults, int64_t *bits)
+{
+    int64_t n_d = NB - n_u - n_p, E = BK * BN;
+    *params = n_u + E * n_d;
+    *mults = BN * n_u + E * n_d;
+    *bits = 2 * NB + n_u * (value_bits + E) + n_d * value_bits * E;
 }
 
 /* The Q-step and the U-step of one ADMM iteration for one layer in GEMM view (Sec. 3.3, Alg. 1 steps 6

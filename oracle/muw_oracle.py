@@ -48,6 +48,13 @@ def lib():
         L.oracle_admm_update.restype = C.c_int
         L.oracle_admm_penalty.argtypes = [p, p, p, i64, dbl, p]
         L.oracle_admm_penalty.restype = dbl
+        L.oracle_block_scores_2d.argtypes = [p, i64, i64, i64, i64, p, p, p]
+        L.oracle_block_scores_2d.restype = C.c_int
+        L.oracle_encode_2d.argtypes = [p, i64, i64, i64, i64, i64, i64, C.c_int, p, p, p]
+        L.oracle_encode_2d.restype = C.c_int
+        L.oracle_counters_2d.argtypes = [i64, i64, i64, i64, i64, i64, C.POINTER(i64), C.POINTER(i64),
+                                         C.POINTER(i64)]
+        L.oracle_counters_2d.restype = None
         L.oracle_omp_threads.argtypes = []
         L.oracle_omp_threads.restype = C.c_int
         _lib = L
@@ -119,6 +126,44 @@ def encode(Wg, B, n_u, n_p, storage):
     if rc != 0:
         raise ValueError("bad arguments")
     return tags, signs, mags, What
+
+
+def block_scores_2d(Wg, BK, BN):
+    Wg = _f64(Wg)
+    N, K = Wg.shape
+    NB = (N // BN) * (K // BK)
+    q, e_p, e_u = (np.empty(NB, dtype=np.float64) for _ in range(3))
+    rc = lib().oracle_block_scores_2d(_ptr(Wg), N, K, BK, BN, _ptr(q), _ptr(e_p), _ptr(e_u))
+    if rc != 0:
+        raise ValueError("non-finite weight")
+    return q, e_p, e_u
+
+
+def encode_2d(Wg, BK, BN, n_u, n_p, storage):
+    """[BK, BN] blocks (BK along K, BN along N).  Returns (tags u8[NB], mags f64[NB], What f64[N,K]),
+    block index j = (n // BN) * (K // BK) + k // BK."""
+    Wg = _f64(Wg)
+    N, K = Wg.shape
+    if BK <= 0 or BN <= 0 or K % BK or N % BN:
+        raise ValueError("N, K must be multiples of the block extents")
+    NB = (N // BN) * (K // BK)
+    tags = np.empty(NB, dtype=np.uint8)
+    mags = np.empty(NB, dtype=np.float64)
+    What = np.empty((N, K), dtype=np.float64)
+    rc = lib().oracle_encode_2d(_ptr(Wg), N, K, BK, BN, int(n_u), int(n_p), int(storage), _ptr(tags),
+                                _ptr(mags), _ptr(What))
+    if rc == -2:
+        raise ValueError("non-finite weight")
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return tags, mags, What
+
+
+def counters_2d(NB, BK, BN, n_u, n_p, value_bits=16):
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    lib().oracle_counters_2d(int(NB), int(BK), int(BN), int(n_u), int(n_p), int(value_bits), C.byref(a),
+                             C.byref(b), C.byref(c))
+    return a.value, b.value, c.value
 
 
 def admm_update(W, U, B, n_u, n_p, storage):

@@ -500,3 +500,109 @@ def test_admm_update_in_bf16_rounds_every_step_to_bf16(oracle):
     assert np.array_equal(Q, T)
     for a in (Q, U_new):
         assert np.array_equal(a, synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(a.astype(np.float32))).reshape(a.shape))
+
+
+# ---- two-dimensional block shapes [BK, BN] (Sec. 3.2, Table 1) ---------------------------------------
+
+@pytest.mark.parametrize("B", [4, 8, 16])
+def test_2d_blocks_one_row_high_are_the_1d_blocks(oracle, B):
+    W = synth.normal_tensor(300 + B, (12, 64), 0.05, "bf16").f64()
+    NB = 12 * 64 // B
+    n_u, n_p = oracle.counts(NB, 0.45, 0.3)
+    tags, signs, mags, What = oracle.encode(W, B, n_u, n_p, oracle.STORE_BF16)
+    tags2, mags2, What2 = oracle.encode_2d(W, B, 1, n_u, n_p, oracle.STORE_BF16)
+    assert np.array_equal(tags, tags2) and np.array_equal(mags, mags2) and np.array_equal(What, What2)
+    q, e_p, e_u = oracle.block_scores(W, B)
+    q2, e_p2, e_u2 = oracle.block_scores_2d(W, B, 1)
+    assert np.array_equal(q, q2) and np.array_equal(e_p, e_p2) and np.array_equal(e_u, e_u2)
+
+
+def test_2d_unified_value_is_the_l2_projection_bruteforce(oracle):
+    """[2,2] block: every sign pattern and a grid of q; minimiser sgn(w), mean|w| over all four weights,
+    minimum sum w^2 - 4 q^2 = the oracle's e_u, and sum w^2 = its e_p."""
+    vals = synth.standard_normal(77, 30 * 4).reshape(30, 2, 2)
+    vals[0] = -0.4
+    vals[1, 0, 1] = 0.0
+    for w in vals:
+        q, e_p, e_u = oracle.block_scores_2d(w, 2, 2)
+        tags, mags, What = oracle.encode_2d(w, 2, 2, 1, 0, oracle.STORE_F32)
+        flat = w.reshape(-1)
+        grid = np.linspace(0.0, 2.0 * np.abs(flat).max() + 1e-9, 2001)
+        best = (np.inf, None)
+        for s in itertools.product([1.0, -1.0], repeat=4):
+            d = ((flat[None, :] - grid[:, None] * np.array(s)[None, :]) ** 2).sum(1)
+            i = int(d.argmin())
+            if d[i] < best[0]:
+                best = (d[i], grid[i])
+        h = grid[1] - grid[0]
+        assert abs(best[1] - q[0]) <= h and abs(q[0] - np.abs(flat).mean()) <= 1e-15
+        assert abs(e_u[0] - ((flat ** 2).sum() - 4 * q[0] ** 2)) <= 1e-12
+        assert best[0] >= e_u[0] - 1e-12 and best[0] <= e_u[0] + 4 * h * h
+        assert abs(e_p[0] - (flat ** 2).sum()) <= 1e-15
+        assert tags[0] == oracle.TAG_UNIFIED and np.allclose(np.abs(What), mags[0])
+        nz = w != 0
+        assert np.all(np.sign(What[nz]) == np.sign(w[nz]))
+
+
+@pytest.mark.parametrize("BK,BN,n_p,n_u", [(2, 2, 2, 2), (2, 2, 0, 3), (4, 2, 3, 1), (2, 3, 1, 2)])
+def test_2d_selection_is_min_distortion_bruteforce(oracle, BK, BN, n_p, n_u):
+    """All subsets: the pruned set minimises the distortion of pruning, the unified set minimises the
+    distortion of unifying among what is left (distances computed here from the block's own elements)."""
+    N, K = 2 * BN, 4 * BK                                # 8 blocks
+    W = rng_matrix(500 + BK * 10 + BN, N, K)
+    NB = 8
+    blocks = [W[(j // 4) * BN:(j // 4 + 1) * BN, (j % 4) * BK:(j % 4 + 1) * BK].reshape(-1) for j in range(NB)]
+    cost_p = [float((b ** 2).sum()) for b in blocks]
+    cost_u = [float(((np.abs(b) - np.abs(b).mean()) ** 2).sum()) for b in blocks]
+    tags, mags, What = oracle.encode_2d(W, BK, BN, n_u, n_p, oracle.STORE_F32)
+    best_p = min(itertools.combinations(range(NB), n_p), key=lambda S: sum(cost_p[j] for j in S))
+    assert set(np.flatnonzero(tags == oracle.TAG_PRUNED)) == set(best_p)
+    rest = [j for j in range(NB) if j not in best_p]
+    best_u = min(itertools.combinations(rest, n_u), key=lambda S: sum(cost_u[j] for j in S))
+    assert set(np.flatnonzero(tags == oracle.TAG_UNIFIED)) == set(best_u)
+    total = sum(cost_p[j] for j in best_p) + sum(cost_u[j] for j in best_u)
+    assert abs(((W - What) ** 2).sum() - total) <= 1e-6 * max(total, 1.0)
+
+
+def test_2d_block_extents_lie_along_k_then_n(oracle):
+    """A planted rectangle of tiny weights, BK = 4 columns wide and BN = 2 rows high, is the one block
+    that gets pruned; a transposed reading of the shape would cut it in pieces."""
+    BK, BN, N, K = 4, 2, 6, 16
+    W = 1.0 + np.abs(rng_matrix(9, N, K))
+    W[2:4, 8:12] = 1e-3
+    tags, mags, What = oracle.encode_2d(W, BK, BN, 0, 1, oracle.STORE_F32)
+    KB = K // BK
+    assert list(np.flatnonzero(tags == oracle.TAG_PRUNED)) == [1 * KB + 2]
+    expect = W.copy()
+    expect[2:4, 8:12] = 0.0
+    assert np.array_equal(What, expect)
+    # unify a single block with mixed signs: its four-by-two rectangle shares one magnitude
+    W2 = rng_matrix(10, N, K)
+    W2[4:6, 0:4] = np.array([[0.5, -0.5, 0.5, -0.5], [-0.5, 0.5, 0.5, 0.5]])
+    tags, mags, What = oracle.encode_2d(W2, BK, BN, 1, 0, oracle.STORE_F32)
+    assert list(np.flatnonzero(tags == oracle.TAG_UNIFIED)) == [2 * KB + 0] and mags[2 * KB] == 0.5
+    assert np.array_equal(What[4:6, 0:4], W2[4:6, 0:4])
+
+
+def test_2d_table1_row(oracle):
+    pv = paper_values()
+    NB = 1000
+    params, mults, bits = oracle.counters_2d(NB, 2, 2, NB, 0)
+    assert NB * 4 / params == pv["table1_[2,2]_storage_reduction"]
+    assert NB * 4 / mults == pv["table1_[2,2]_multiplier_reduction"]
+    assert bits == NB * (2 + 16 + 4)
+    for B in (4, 8):                                     # one row high: the [B,1] counters
+        assert oracle.counters_2d(NB, B, 1, 600, 300) == oracle.counters(NB, B, 600, 300)
+    # the two multiplications of Sec. 3.2's example: a unified 2x2 block, two activation rows -> 4
+    assert 2 * oracle.counters_2d(1, 2, 2, 1, 0)[1] == pv["fig2_block_multipliers_unified"]
+    assert 2 * oracle.counters_2d(1, 2, 2, 0, 0)[1] == pv["fig2_block_multipliers_dense"]
+
+
+def test_2d_ties_and_sign_rule(oracle):
+    W = np.zeros((4, 8))
+    tags, mags, What = oracle.encode_2d(W, 4, 2, 1, 2, oracle.STORE_BF16)
+    assert list(tags) == [oracle.TAG_PRUNED, oracle.TAG_PRUNED, oracle.TAG_UNIFIED, oracle.TAG_DENSE]
+    W = np.array([[0.0, -0.0, 3.0, -1.0], [1.0, -1.0, 1.0, -1.0]])
+    tags, mags, What = oracle.encode_2d(W, 4, 2, 1, 0, oracle.STORE_F32)
+    assert mags[0] == 1.0 and np.array_equal(What, [[1, 1, 1, -1], [1, -1, 1, -1]])
+    assert not np.signbit(What[0, 1])
