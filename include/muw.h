@@ -24,6 +24,16 @@
  *  - Supported: B in {4, 8, 16}; storage (magnitudes and dense blocks) bf16 or fp32; activations of
  *    the same type as the storage; outputs fp32 or bf16.
  *  - The encoded blob is position independent (offsets only) and may be copied or saved byte for byte.
+ *
+ * Two-dimensional blocks (Sec. 3.2 and Table 1: the block shape is free and should match the compute unit of
+ * the target).  With desc.B = 16 and desc.BN = 32 a block is the [16, 32] rectangle W[32 s .. 32 s + 31]
+ * [16 kc .. 16 kc + 15] -- the A operand of the 32x32x16 bf16 matrix-core instruction -- so a PRUNED block
+ * removes whole matrix instructions, and a UNIFIED block shares one magnitude q = mean |w| over its 512 weights.
+ * Block index j = s * (K / 16) + kc; the sums of the scores run over the block's rows in order and inside a row
+ * over k in order.  Restrictions: bf16, MUW_LAYOUT_NK, N % 32 == 0, K % 16 == 0.  Supported entry points:
+ * muw_encode_sizes, muw_encode, muw_export (signs_dev must be NULL: the signs are those of muw_decode's
+ * output), muw_decode, muw_compressed_bytes, muw_gemm (no workspace; X 16-byte aligned, ldx % 8 == 0); the
+ * others return MUW_EUNSUPPORTED.
  */
 #ifndef MUW_H
 #define MUW_H
@@ -65,7 +75,8 @@ typedef struct {
                              divisible by 4 (written by muw_encode; 0 = unknown: the fast small-M
                              kernel is then not used).  For muw_gemm_grouped both must be >= the
                              values of every layer in the group. */
-    int32_t reserved;       /* keep 0 */
+    int32_t BN;             /* block extent along N: 0 or 1 = the [B,1] blocks above; 32 (with B = 16) = blocks
+                               shaped like a matrix-core operand, see "Two-dimensional blocks" below */
     int64_t n_unified;    /* number of UNIFIED blocks (written by muw_encode) */
     int64_t n_pruned;     /* number of PRUNED blocks  (written by muw_encode) */
 } muw_desc;

@@ -25,7 +25,7 @@ EXPORTED = ["muw_version", "muw_status_str", "muw_counts", "muw_encode_sizes", "
 
 class muw_desc(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("B", C.c_int32), ("KH", C.c_int32),
-                ("KW", C.c_int32), ("Cin", C.c_int32), ("wdtype", C.c_int32), ("max_tile_bytes", C.c_int32), ("max_quad_bytes", C.c_int32), ("reserved", C.c_int32),
+                ("KW", C.c_int32), ("Cin", C.c_int32), ("wdtype", C.c_int32), ("max_tile_bytes", C.c_int32), ("max_quad_bytes", C.c_int32), ("BN", C.c_int32),
                 ("n_unified", C.c_int64), ("n_pruned", C.c_int64)]
 
 
@@ -110,8 +110,8 @@ def muw_counts(NB, r_unify, r_prune):
     return nu.value, np_.value
 
 
-def make_desc(N, K, B, wdtype, KH=1, KW=1, Cin=None):
-    return muw_desc(N=N, K=K, B=B, KH=KH, KW=KW, Cin=K if Cin is None else Cin, wdtype=wdtype, max_tile_bytes=0, max_quad_bytes=0, reserved=0,
+def make_desc(N, K, B, wdtype, KH=1, KW=1, Cin=None, BN=0):
+    return muw_desc(N=N, K=K, B=B, KH=KH, KW=KW, Cin=K if Cin is None else Cin, wdtype=wdtype, max_tile_bytes=0, max_quad_bytes=0, BN=BN,
                     n_unified=0, n_pruned=0)
 
 
@@ -130,19 +130,20 @@ class EncodedLayer:
 
     @property
     def NB(self):
-        return self.desc.N * (self.desc.K // self.desc.B)
+        return (self.desc.N // max(self.desc.BN, 1)) * (self.desc.K // self.desc.B)
 
     @property
     def compressed_bytes(self):
         return lib.muw_compressed_bytes(C.byref(self.desc))
 
 
-def muw_encode(W, B, r_unify, r_prune):
-    """W: cuda tensor [N, K] (linear) or [Cout, Cin, KH, KW] (convolution), fp32 or bf16, contiguous."""
+def muw_encode(W, B, r_unify, r_prune, BN=0):
+    """W: cuda tensor [N, K] (linear) or [Cout, Cin, KH, KW] (convolution), fp32 or bf16, contiguous.
+    BN = 32 with B = 16 selects the two-dimensional [16, 32] blocks (linear layers, bf16)."""
     assert W.is_cuda and W.is_contiguous()
     if W.dim() == 2:
         N, K = W.shape
-        desc, layout = make_desc(N, K, B, _dtype_code(W)), MUW_LAYOUT_NK
+        desc, layout = make_desc(N, K, B, _dtype_code(W), BN=BN), MUW_LAYOUT_NK
     elif W.dim() == 4:
         Cout, Cin, KH, KW = W.shape
         desc = make_desc(Cout, Cin * KH * KW, B, _dtype_code(W), KH, KW, Cin)
@@ -196,6 +197,8 @@ def muw_export(layer):
     tags = torch.empty(NB, dtype=torch.uint8, device=dev)
     signs = torch.empty(NB, dtype=torch.int16, device=dev)
     mags = torch.empty(NB, dtype=_TORCH_DTYPE[layer.desc.wdtype], device=dev)
+    if layer.desc.BN > 1:
+        signs = None        # two-dimensional blocks: the signs are those of muw_decode's output
     _check(lib.muw_export(C.byref(layer.desc), _ptr(layer.blob), _ptr(tags), _ptr(signs), _ptr(mags),
                           _stream()), "muw_export")
     return tags, signs, mags

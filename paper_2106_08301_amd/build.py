@@ -3,8 +3,8 @@
     python -m paper_2106_08301_amd.build [--force]
 
 Each .hip file is compiled on its own and the objects are linked into
-paper_2106_08301_amd/libmuw.so.  muw_encode.hip is compiled with -ffp-contract=off because the
-bit patterns of its fp64 block scores decide the block selection.
+paper_2106_08301_amd/libmuw.so.  The encoders are compiled with -ffp-contract=off because the
+bit patterns of their fp64 block scores decide the block selection.
 """
 import os
 import subprocess
@@ -19,7 +19,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-PER_FILE = {"muw_encode.hip": ["-ffp-contract=off"]}
+PER_FILE = {"muw_encode.hip": ["-ffp-contract=off"], "muw_block2d_encode.hip": ["-ffp-contract=off"]}
 EXTRA = os.environ.get("MUW_EXTRA_HIPCC_FLAGS", "").split()  # e.g. -DMUW_STREAM_WAVES=4 for experiments
 
 

@@ -2,6 +2,7 @@
 // No device memory is allocated here or anywhere else in the library.
 #include <math.h>
 
+#include "muw_block2d.hpp"
 #include "muw_internal.hpp"
 
 using namespace muw;
@@ -22,6 +23,22 @@ muw_status check_desc(const muw_desc *d)
     if (int64_t(d->KH) * d->KW * d->Cin != d->K) return MUW_ESHAPE;
     if (!supported_block(d->B)) return MUW_EUNSUPPORTED;
     if (d->N > (int64_t(1) << 31) || d->K > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    if (d->BN < 0) return MUW_EINVAL;
+    if (d->BN > 1) {  // MFMA-operand-shaped blocks: [16, 32], bf16, linear layers
+        if (d->BN != kB2N || d->B != kB2K || d->wdtype != MUW_BF16 || d->KH != 1 || d->KW != 1) return MUW_EUNSUPPORTED;
+        if (d->N % kB2N != 0) return MUW_ESHAPE;
+    }
+    return MUW_OK;
+}
+
+int64_t block_count(const muw_desc *d) { return (d->N / (d->BN > 1 ? d->BN : 1)) * (d->K / d->B); }
+
+// Layout of a [16, 32]-block layer from the counts muw_encode left in the descriptor.
+muw_status layout2_of(const muw_desc *d, Layout2 *L)
+{
+    const int64_t NB = block_count(d);
+    if (d->n_unified < 0 || d->n_pruned < 0 || d->n_unified + d->n_pruned > NB) return MUW_EINVAL;
+    *L = make_layout2(d->N, d->K, d->n_unified, NB - d->n_unified - d->n_pruned);
     return MUW_OK;
 }
 
@@ -77,6 +94,16 @@ muw_status muw_encode_sizes(const muw_desc *desc, double r_unify, double r_prune
     muw_status rc = check_desc(desc);
     if (rc != MUW_OK) return rc;
     if (!blob_bytes || !workspace_bytes) return MUW_EINVAL;
+    if (is_block2d(*desc)) {
+        const int64_t NB2 = block_count(desc);
+        int64_t n_u2, n_p2;
+        rc = muw_counts(NB2, r_unify, r_prune, &n_u2, &n_p2);
+        if (rc != MUW_OK) return rc;
+        const Layout2 L2 = make_layout2(desc->N, desc->K, n_u2, NB2 - n_u2 - n_p2);
+        *blob_bytes = size_t(L2.total);
+        *workspace_bytes = block2d_encode_workspace(L2);
+        return MUW_OK;
+    }
     const Layout L = layout_of(desc);
     const int64_t NB = L.N * L.KB;
     int64_t n_u, n_p;
@@ -100,6 +127,22 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
     rc = muw_encode_sizes(desc, r_unify, r_prune, &need_blob, &need_ws);
     if (rc != MUW_OK) return rc;
     if (blob_bytes < need_blob || ws_bytes < need_ws) return MUW_ENOSPC;
+    if (is_block2d(*desc)) {
+        if (layout != MUW_LAYOUT_NK) return MUW_EUNSUPPORTED;
+        const int64_t NB2 = block_count(desc);
+        int64_t n_u2, n_p2;
+        muw_counts(NB2, r_unify, r_prune, &n_u2, &n_p2);
+        const Layout2 L2 = make_layout2(desc->N, desc->K, n_u2, NB2 - n_u2 - n_p2);
+        bool bad = false;
+        rc = launch_block2d_encode(L2, W_dev, n_u2, n_p2, blob_dev, ws_dev, static_cast<hipStream_t>(hip_stream), &bad);
+        if (rc != MUW_OK) return rc;
+        if (bad) return MUW_ENONFINITE;
+        desc->n_unified = n_u2;
+        desc->n_pruned = n_p2;
+        desc->max_tile_bytes = 0;
+        desc->max_quad_bytes = 0;
+        return MUW_OK;
+    }
     const Layout L = layout_of(desc);
     int64_t n_u, n_p;
     muw_counts(L.N * L.KB, r_unify, r_prune, &n_u, &n_p);
@@ -118,7 +161,7 @@ muw_status muw_encode(muw_desc *desc, const void *W_dev, muw_layout layout, doub
 
 size_t muw_admm_workspace_bytes(const muw_desc *desc)
 {
-    if (check_desc(desc) != MUW_OK) return 0;
+    if (check_desc(desc) != MUW_OK || is_block2d(*desc)) return 0;
     return admm_workspace_bytes(*desc, layout_of(desc));
 }
 
@@ -127,6 +170,7 @@ muw_status muw_admm_update(const muw_desc *desc, const void *W_dev, void *U_dev,
 {
     muw_status rc = check_desc(desc);
     if (rc != MUW_OK) return rc;
+    if (is_block2d(*desc)) return MUW_EUNSUPPORTED;
     if (!W_dev || !U_dev || !Q_dev || !ws_dev) return MUW_EINVAL;
     if (layout != MUW_LAYOUT_NK && layout != MUW_LAYOUT_OIHW) return MUW_EINVAL;
     if (!aligned16(W_dev) || !aligned16(U_dev) || !aligned16(Q_dev) || !aligned16(ws_dev)) return MUW_EINVAL;
@@ -158,6 +202,13 @@ muw_status muw_export(const muw_desc *desc, const void *blob_dev, uint8_t *tags_
     muw_status rc = check_desc(desc);
     if (rc != MUW_OK) return rc;
     if (!blob_dev) return MUW_EINVAL;
+    if (is_block2d(*desc)) {
+        if (signs_dev) return MUW_EINVAL;  // 512 sign bits per block: read them off muw_decode's output
+        Layout2 L2;
+        rc = layout2_of(desc, &L2);
+        if (rc != MUW_OK) return rc;
+        return launch_block2d_export(L2, blob_dev, tags_dev, mags_dev, static_cast<hipStream_t>(hip_stream));
+    }
     return launch_export(*desc, layout_of(desc), blob_dev, tags_dev, signs_dev, mags_dev,
                          static_cast<hipStream_t>(hip_stream));
 }
@@ -167,23 +218,30 @@ muw_status muw_decode(const muw_desc *desc, const void *blob_dev, void *What_dev
     muw_status rc = check_desc(desc);
     if (rc != MUW_OK) return rc;
     if (!blob_dev || !What_dev) return MUW_EINVAL;
+    if (is_block2d(*desc)) {
+        Layout2 L2;
+        rc = layout2_of(desc, &L2);
+        if (rc != MUW_OK) return rc;
+        return launch_block2d_decode(L2, blob_dev, What_dev, static_cast<hipStream_t>(hip_stream));
+    }
     return launch_decode(*desc, layout_of(desc), blob_dev, What_dev, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t muw_compressed_bytes(const muw_desc *desc)
 {
     if (check_desc(desc) != MUW_OK) return 0;
-    const uint64_t NB = uint64_t(desc->N) * uint64_t(desc->K / desc->B);
+    const uint64_t NB = uint64_t(block_count(desc));
     const uint64_t n_u = uint64_t(desc->n_unified), n_p = uint64_t(desc->n_pruned);
     if (n_u + n_p > NB) return 0;
     const uint64_t n_d = NB - n_u - n_p, vbits = 8u * uint64_t(value_bytes(desc->wdtype));
-    const uint64_t bits = 2 * NB + n_u * (vbits + uint64_t(desc->B)) + n_d * vbits * uint64_t(desc->B);
+    const uint64_t E = uint64_t(desc->B) * uint64_t(desc->BN > 1 ? desc->BN : 1);  // weights per block
+    const uint64_t bits = 2 * NB + n_u * (vbits + E) + n_d * vbits * E;
     return size_t((bits + 7) / 8);
 }
 
 size_t muw_gemm_workspace_bytes(const muw_desc *desc, int64_t M)
 {
-    if (check_desc(desc) != MUW_OK || M < 0) return 0;
+    if (check_desc(desc) != MUW_OK || M < 0 || is_block2d(*desc)) return 0;
     return gemm_workspace_bytes(*desc, layout_of(desc), M);
 }
 
@@ -199,6 +257,14 @@ muw_status muw_gemm(const muw_desc *desc, const void *blob_dev, const void *X_de
     if (int(xdtype) != desc->wdtype) return MUW_EUNSUPPORTED;
     if (ldx < desc->K || ldy < desc->N) return MUW_ESHAPE;
     if (M > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    if (is_block2d(*desc)) {
+        if (M >= (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+        Layout2 L2;
+        rc = layout2_of(desc, &L2);
+        if (rc != MUW_OK) return rc;
+        return launch_block2d_gemm(L2, blob_dev, X_dev, M, ldx, Y_dev, int(ydtype), ldy,
+                                   static_cast<hipStream_t>(hip_stream));
+    }
     const Layout L = layout_of(desc);
     const size_t need = gemm_workspace_bytes(*desc, L, M);
     if (need && (!ws_dev || ws_bytes < need)) return MUW_ENOSPC;
@@ -224,7 +290,7 @@ muw_status muw_gemm_grouped(const muw_desc *desc, int32_t G, const void *const *
     if (G == 0 || M == 0) return MUW_OK;
     if (!blobs_dev || !X_ptrs_dev || !Y_ptrs_dev) return MUW_EINVAL;
     if (int(xdtype) != desc->wdtype) return MUW_EUNSUPPORTED;
-    if (M > 16 || G > 65535) return MUW_EUNSUPPORTED;
+    if (M > 16 || G > 65535 || is_block2d(*desc)) return MUW_EUNSUPPORTED;
     const Layout L = layout_of(desc);
     GemmArgs a{};
     a.blobs = blobs_dev;
@@ -242,6 +308,7 @@ size_t muw_conv2d_workspace_bytes(const muw_desc *desc, int64_t Nb, int64_t H, i
                                   int32_t pad)
 {
     if (check_desc(desc) != MUW_OK || Nb < 0 || H <= 0 || W <= 0 || stride < 1 || pad < 0) return 0;
+    if (is_block2d(*desc)) return 0;
     return conv2d_workspace_bytes(*desc, layout_of(desc), Nb, H, W, stride, pad);
 }
 
@@ -253,6 +320,7 @@ muw_status muw_conv2d(const muw_desc *desc, const void *blob_dev, const void *X_
     if (rc != MUW_OK) return rc;
     if (Nb < 0 || H <= 0 || W <= 0 || stride < 1 || pad < 0) return MUW_EINVAL;
     if (!valid_dtype(xdtype) || !valid_dtype(ydtype)) return MUW_EINVAL;
+    if (is_block2d(*desc)) return MUW_EUNSUPPORTED;
     if (H + 2 * int64_t(pad) < desc->KH || W + 2 * int64_t(pad) < desc->KW) return MUW_ESHAPE;
     if (Nb == 0) return MUW_OK;
     if (!blob_dev || !X_dev || !Y_dev) return MUW_EINVAL;

@@ -1,0 +1,78 @@
+// muw_block2d.hpp -- layers encoded in MFMA-operand-shaped blocks (private).
+//
+// Sec. 3.2 leaves the block shape open and asks for one that matches the compute unit of the target.  On
+// gfx950 that unit is the A operand of v_mfma_f32_32x32x16_bf16: 32 output rows x 16 contraction indices.
+// With blocks of exactly that shape ([16, 32] in the paper's [K extent, N extent] notation of Table 1)
+//   - a PRUNED block removes one whole MFMA per 32 activation rows, not just its bytes,
+//   - a UNIFIED block is one bf16 magnitude and 512 sign bits, decoded by the wavefront that owns the strip
+//     straight into its operand registers (lane l holds row l % 32, k = 8 (l / 32) .. + 7 of the block),
+//   - a DENSE block is stored in that register order: one 16-byte load per lane.
+//
+// Geometry: strip = 32 consecutive output rows; block (s, kc) = strip s x k in [16 kc, 16 kc + 16);
+// block index j = s * KC + kc (KC = K / 16).  Storage is bf16, N % 32 == 0, K % 16 == 0.
+//
+// Blob = [64-byte header]
+//        [present bitmaps: NS x W64 64-bit words, bit kc % 64 of word kc / 64 set = block not PRUNED]
+//        [dense bitmaps:   same shape, bit set = block DENSE]           (2 bits per block in all)
+//        [directory: (NS + 1) x {u32 first UNIFIED rank, u32 first DENSE rank} of each strip]
+//        [magnitudes: one bf16 per UNIFIED block, in block order]       (64-byte aligned)
+//        [sign planes: 64 bytes per UNIFIED block: plane i (i < 8, 64 bits) bit l = sign of the weight
+//         lane l holds at position i, i.e. W[32 s + l % 32][16 kc + 8 (l / 32) + i] < 0]
+//        [dense payload: 1024 bytes per DENSE block, lane l's 8 values at byte 16 l]
+// A strip's payload is contiguous and in kc order, so a wavefront walks it with two running counters.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "muw_internal.hpp"
+
+namespace muw {
+
+constexpr int kB2K = 16;   // block extent along K
+constexpr int kB2N = 32;   // block extent along N
+constexpr uint32_t kMagic2 = 0x3257554du;  // "MUW2"
+
+struct Layout2 {
+    int64_t N, K;
+    int64_t NS, KC, W64, NB;   // strips, block columns, bitmap words per strip, blocks
+    int64_t n_u, n_d;
+    uint64_t present_off, densemap_off, dir_off, mags_off, signs_off, dense_off, total;
+};
+
+__host__ __device__ inline uint64_t align64(uint64_t x) { return (x + 63) & ~uint64_t(63); }
+
+__host__ __device__ inline Layout2 make_layout2(int64_t N, int64_t K, int64_t n_u, int64_t n_d)
+{
+    Layout2 L;
+    L.N = N;
+    L.K = K;
+    L.NS = N / kB2N;
+    L.KC = K / kB2K;
+    L.W64 = (L.KC + 63) / 64;
+    L.NB = L.NS * L.KC;
+    L.n_u = n_u;
+    L.n_d = n_d;
+    L.present_off = 64;
+    L.densemap_off = L.present_off + uint64_t(L.NS) * uint64_t(L.W64) * 8u;
+    L.dir_off = L.densemap_off + uint64_t(L.NS) * uint64_t(L.W64) * 8u;
+    L.mags_off = align64(L.dir_off + uint64_t(L.NS + 1) * 8u);
+    L.signs_off = align64(L.mags_off + uint64_t(n_u) * 2u);
+    L.dense_off = L.signs_off + uint64_t(n_u) * 64u;
+    L.total = align64(L.dense_off + uint64_t(n_d) * 1024u);
+    return L;
+}
+
+inline bool is_block2d(const muw_desc &d) { return d.BN > 1; }
+
+// muw_block2d_encode.hip
+size_t block2d_encode_workspace(const Layout2 &L);
+muw_status launch_block2d_encode(const Layout2 &L, const void *W, int64_t n_u, int64_t n_p, void *blob, void *ws,
+                                 hipStream_t st, bool *nonfinite);
+muw_status launch_block2d_export(const Layout2 &L, const void *blob, uint8_t *tags, void *mags, hipStream_t st);
+muw_status launch_block2d_decode(const Layout2 &L, const void *blob, void *What, hipStream_t st);
+
+// muw_block2d_gemm.hip
+muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X, int64_t M, int64_t ldx, void *Y,
+                               int ydtype, int64_t ldy, hipStream_t st);
+
+}  // namespace muw

@@ -1,0 +1,294 @@
+// muw_block2d_gemm.hip -- Y = X * W^^T (Sec. 3.2) for layers encoded in [16, 32] blocks (muw_block2d.hpp).
+//
+// A workgroup of 8 wavefronts owns 32*MSUB activation rows and 256 output columns; wavefront w owns the
+// 32-row strip w of those columns for ALL of K and keeps its MSUB 32x32 accumulators in registers.
+//   - The activation tile goes HBM/L2 -> LDS in slabs of 128 k with global_load_lds (no registers), two
+//     slabs in flight (one being read, one landing).  A row of a slab is 256 contiguous bytes on both
+//     sides; its 16-byte chunks are stored XOR-swizzled with the row number so that the 64 lanes of a
+//     fragment read (32 rows x 2 chunks) hit distinct banks.
+//   - A wavefront walks the present-bitmap of its strip: a PRUNED block costs nothing at all -- no bytes,
+//     no decode, no MFMA (Sec. 3.2: pruned blocks are skipped).  A UNIFIED block arrives through the scalar
+//     cache (magnitude + 8 sign planes of 64 bits = 16 scalar registers): plane i IS the lane mask "the
+//     lane's i-th weight is negative", so the decode is two selects and one merge per register.  A DENSE
+//     block is one 16-byte vector load per lane.  The next block's payload is requested before the
+//     current block's MFMAs are issued.
+//   - Per surviving block and 32 activation rows: one ds_read_b128 and one v_mfma_f32_32x32x16_bf16 with
+//     the weights as the A operand, so that a lane ends up with 4 consecutive output columns per register
+//     quad and the epilogue writes 16 bytes per lane.
+// Waves of one workgroup finish their strips' blocks of a slab at different times and meet at one barrier
+// per slab; a second resident workgroup per compute unit fills those gaps.
+#include "muw_block2d.hpp"
+#include "muw_decode.hpp"
+
+namespace muw {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(4))) uint64_t c_u64;
+typedef const __attribute__((address_space(4))) uint32_t c_u32;
+typedef __attribute__((address_space(1))) void global_void;
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr int kWaves = 8;
+constexpr int kSlabK = 128;
+
+struct B2Args {
+    const uint8_t *blob;
+    const uint16_t *X;
+    void *Y;
+    int64_t ldx, ldy;
+    int32_t M, K;
+    uint32_t NS, W64;
+    uint64_t present_off, densemap_off, dir_off, mags_off, signs_off, dense_off;
+    uint32_t n_ntiles, chunk, total;
+    int32_t ydtype, vec_store;
+};
+
+template <int OFF>
+__device__ inline u32x4 lds_read_b128_at(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+template <int MSUB>
+__global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
+{
+    constexpr int MT = 32 * MSUB;
+    constexpr uint32_t kSlabBytes = uint32_t(MT) * kSlabK * 2u;
+    __shared__ __attribute__((aligned(1024))) uint8_t xs[2 * kSlabBytes];
+
+    // Consecutive workgroup ids go to consecutive XCDs; give each XCD a contiguous run of the M-major tile
+    // list, so the workgroups resident on one XCD share their activation rows in its L2.
+    const uint32_t slot = blockIdx.x >> 3, xcd = blockIdx.x & 7u;
+    const uint32_t t = xcd * a.chunk + slot;
+    if (slot >= a.chunk || t >= a.total) return;
+    const uint32_t mtile = t / a.n_ntiles, ntile = t % a.n_ntiles;
+
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t strip = ntile * kWaves + wave;
+    const bool live = strip < a.NS;
+    const uint32_t m0 = mtile * MT;
+    const uint32_t nslabs = (uint32_t(a.K) + kSlabK - 1) / kSlabK;
+
+    // ---- activation slabs: DMA instruction i of this wave fills rows (8 i + wave) * 4 .. + 3 of the tile
+    const uint32_t sub = uint32_t(lane) >> 4, pos = uint32_t(lane) & 15u;       // row inside the 4, chunk position
+    const uint32_t swz = pos ^ ((wave * 4u + sub) & 15u);                        // chunk of the row stored at `pos`
+    const uint16_t *xrow[MSUB];
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i) {
+        uint32_t row = m0 + (uint32_t(i) * 8u + wave) * 4u + sub;
+        if (row >= uint32_t(a.M)) row = uint32_t(a.M) - 1u;
+        xrow[i] = a.X + int64_t(row) * a.ldx;
+    }
+    auto issue_slab = [&](uint32_t j) __attribute__((always_inline)) {
+        uint32_t k = j * kSlabK + swz * 8u;
+        if (k >= uint32_t(a.K)) k = j * kSlabK;  // past the last column: any valid address, no block reads it
+        uint8_t *dst = xs + (j & 1u) * kSlabBytes + wave * 1024u;
+#pragma unroll
+        for (int i = 0; i < MSUB; ++i)
+            __builtin_amdgcn_global_load_lds((global_void *)(xrow[i] + k), (lds_void *)(dst + i * 8192), 16, 0, 0);
+    };
+
+    // ---- fragment reads: lane (m = lane % 32, h = lane / 32) wants chunk 2 kc + h of row 32 mt + m
+    const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t *)xs));
+    const uint32_t frag_base = lds_base + (uint32_t(lane) & 31u) * 256u;
+    const uint32_t frag_swz = (uint32_t(lane) >> 5) ^ (uint32_t(lane) & 15u);
+
+    // ---- the strip's blocks
+    c_u64 *present = (c_u64 *)(a.blob + a.present_off) + uint64_t(strip) * a.W64;
+    c_u64 *densemap = (c_u64 *)(a.blob + a.densemap_off) + uint64_t(strip) * a.W64;
+    c_u32 *mags32 = (c_u32 *)(a.blob + a.mags_off);
+    uint32_t g = 0, ru = 0, rd = 0;
+    uint64_t pm = 0, dm = 0;
+    if (live) {
+        c_u32 *dir = (c_u32 *)(a.blob + a.dir_off) + 2u * strip;
+        ru = dir[0];
+        rd = dir[1];
+        pm = present[0];
+        dm = densemap[0];
+    }
+    // Two register sets take turns: while the MFMAs of the block in one set run, the payload of the strip's
+    // next block is on its way into the other (scalar loads for a UNIFIED block, one vector load per lane for
+    // a DENSE one).  The walk is one loop over the strip's surviving blocks; whenever the next block lies in a
+    // later slab the wave first passes the barriers in between, so every wave passes nslabs barriers in all.
+    constexpr uint32_t kNone = 0x7fffffffu;
+    struct Blk {
+        uint32_t kc, qword, qshift;
+        bool dense;
+        uint64_t plane[8];
+        u32x4 raw;
+    };
+    const uint8_t *dense_lane = a.blob + a.dense_off + uint32_t(lane) * 16u;
+    auto fetch = [&](Blk &n) __attribute__((always_inline)) {
+        while (pm == 0 && g + 1 < a.W64 && live) {
+            ++g;
+            pm = present[g];
+            dm = densemap[g];
+        }
+        if (pm == 0) {
+            n.kc = kNone;
+            return;
+        }
+        const uint32_t b = uint32_t(__builtin_ctzll(pm));
+        pm &= pm - 1;
+        n.kc = g * 64u + b;
+        n.dense = (dm >> b) & 1u;
+        if (n.dense) {
+            n.raw = *reinterpret_cast<const u32x4 *>(dense_lane + uint64_t(rd) * 1024u);
+            ++rd;
+        } else {
+            c_u64 *pl = (c_u64 *)(a.blob + a.signs_off + uint64_t(ru) * 64u);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) n.plane[i] = pl[i];
+            n.qword = mags32[ru >> 1];
+            n.qshift = (ru & 1u) * 16u;
+            ++ru;
+        }
+    };
+
+    f32x16 acc[MSUB];
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+
+    // slab `have` is the one the workgroup may read (-1: none yet)
+    int32_t have = -1;
+    auto next_slab = [&]() __attribute__((always_inline)) {
+        ++have;
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of slab `have` has landed
+        __syncthreads();                     // ... and everybody's; everybody is done with the slab before it
+        if (uint32_t(have) + 1u < nslabs) issue_slab(uint32_t(have) + 1u);
+    };
+    auto step = [&](Blk &c, Blk &n) __attribute__((always_inline)) {
+        while (have < int32_t(c.kc >> 3)) next_slab();
+        const uint32_t addr = frag_base + (uint32_t(have) & 1u) * kSlabBytes + ((((c.kc & 7u) * 2u) ^ frag_swz) << 4);
+        u32x4 xf[MSUB];
+        if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
+        if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
+        if constexpr (MSUB >= 4) {
+            xf[2] = lds_read_b128_at<16384>(addr);
+            xf[3] = lds_read_b128_at<24576>(addr);
+        }
+        u32x4 wf;
+        if (c.dense) {
+            wf = c.raw;
+        } else {
+            const uint32_t q = (c.qword >> c.qshift) & 0xffffu;
+            const uint32_t qq = q | (q << 16), qn = qq ^ 0x80008000u;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t lo = __builtin_amdgcn_inverse_ballot_w64(c.plane[2 * d]) ? qn : qq;
+                const uint32_t hi = __builtin_amdgcn_inverse_ballot_w64(c.plane[2 * d + 1]) ? qn : qq;
+                wf[d] = (lo & 0xffffu) | (hi & 0xffff0000u);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xf[0]));
+#pragma unroll
+        for (int i = 1; i < MSUB; ++i) asm volatile("" : "+v"(xf[i]));
+        fetch(n);
+#pragma unroll
+        for (int i = 0; i < MSUB; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf),
+                                                             __builtin_bit_cast(bf16x8, xf[i]), acc[i], 0, 0, 0);
+    };
+
+    issue_slab(0);
+    Blk A, B;
+    fetch(A);
+    for (;;) {
+        if (A.kc == kNone) break;
+        step(A, B);
+        if (B.kc == kNone) break;
+        step(B, A);
+    }
+    while (have + 1 < int32_t(nslabs)) next_slab();  // the barriers of the slabs after the strip's last block
+
+    // ---- epilogue: lane (m = lane % 32, h = lane / 32) holds columns 8 b + 4 h .. + 3 of its row in
+    // registers 4 b .. 4 b + 3 of each accumulator
+    if (!live) return;
+    const uint32_t n_lane = strip * kB2N + (uint32_t(lane) >> 5) * 4u;
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i) {
+        const uint32_t m = m0 + uint32_t(i) * 32u + (uint32_t(lane) & 31u);
+        if (m >= uint32_t(a.M)) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t idx = int64_t(m) * a.ldy + n_lane + 8 * b;
+            const float v0 = acc[i][4 * b], v1 = acc[i][4 * b + 1], v2 = acc[i][4 * b + 2], v3 = acc[i][4 * b + 3];
+            if (a.ydtype == MUW_F32) {
+                float *y = static_cast<float *>(a.Y) + idx;
+                if (a.vec_store) {
+                    *reinterpret_cast<float4 *>(y) = make_float4(v0, v1, v2, v3);
+                } else {
+                    y[0] = v0;
+                    y[1] = v1;
+                    y[2] = v2;
+                    y[3] = v3;
+                }
+            } else {
+                uint16_t *y = static_cast<uint16_t *>(a.Y) + idx;
+                const uint32_t p0 = uint32_t(f32_to_bf16_rne(v0)) | (uint32_t(f32_to_bf16_rne(v1)) << 16);
+                const uint32_t p1 = uint32_t(f32_to_bf16_rne(v2)) | (uint32_t(f32_to_bf16_rne(v3)) << 16);
+                if (a.vec_store) {
+                    *reinterpret_cast<uint2 *>(y) = make_uint2(p0, p1);
+                } else {
+                    y[0] = uint16_t(p0);
+                    y[1] = uint16_t(p0 >> 16);
+                    y[2] = uint16_t(p1);
+                    y[3] = uint16_t(p1 >> 16);
+                }
+            }
+        }
+    }
+}
+
+template <int MSUB>
+muw_status launch(const B2Args &a0, uint32_t n_mtiles, hipStream_t st)
+{
+    B2Args a = a0;
+    a.total = n_mtiles * a.n_ntiles;
+    a.chunk = (a.total + 7u) / 8u;
+    k_block2d_gemm_bf16<MSUB><<<dim3(a.chunk * 8u), dim3(kWaves * 64), 0, st>>>(a);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X, int64_t M, int64_t ldx, void *Y,
+                               int ydtype, int64_t ldy, hipStream_t st)
+{
+    // the DMA moves 16-byte chunks of activation rows
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) || (ldx & 7)) return MUW_EUNSUPPORTED;
+    B2Args a{};
+    a.blob = static_cast<const uint8_t *>(blob);
+    a.X = static_cast<const uint16_t *>(X);
+    a.Y = Y;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.M = int32_t(M);
+    a.K = int32_t(L.K);
+    a.NS = uint32_t(L.NS);
+    a.W64 = uint32_t(L.W64);
+    a.present_off = L.present_off;
+    a.densemap_off = L.densemap_off;
+    a.dir_off = L.dir_off;
+    a.mags_off = L.mags_off;
+    a.signs_off = L.signs_off;
+    a.dense_off = L.dense_off;
+    a.n_ntiles = uint32_t((L.NS + kWaves - 1) / kWaves);
+    a.ydtype = ydtype;
+    const uint32_t ybytes = ydtype == MUW_F32 ? 4u : 2u;
+    a.vec_store = ((reinterpret_cast<uintptr_t>(Y) & (4u * ybytes - 1u)) == 0 && (ldy & 3) == 0) ? 1 : 0;
+    if (M <= 32) return launch<1>(a, 1, st);
+    if (M <= 64) return launch<2>(a, 1, st);
+    return launch<4>(a, uint32_t((M + 127) / 128), st);
+}
+
+}  // namespace muw

@@ -69,4 +69,29 @@ __device__ inline uint16_t f32_to_bf16_rne(float v)
     return uint16_t(b >> 16);
 }
 
+// fp64 -> bf16 bits, one rounding to nearest even, for finite q >= 0.
+__device__ inline uint16_t f64_to_bf16_rne(double q)
+{
+    const uint64_t b = uint64_t(__double_as_longlong(q));
+    const int e = int(b >> 52) & 0x7ff;
+    const uint64_t mant = b & ((uint64_t(1) << 52) - 1);
+    if (e == 0) return 0;            // zero or fp64 subnormal: far below half the smallest bf16
+    const int E = e - 1023 + 127;    // biased bf16 exponent
+    if (E >= 255) return 0x7f80;
+    if (E >= 1) {
+        uint32_t r = (uint32_t(E) << 7) | uint32_t(mant >> 45);
+        const uint64_t rem = mant & ((uint64_t(1) << 45) - 1), half = uint64_t(1) << 44;
+        if (rem > half || (rem == half && (r & 1u))) ++r;  // a carry runs into the exponent
+        return uint16_t(r);
+    }
+    // bf16 subnormal: multiples of 2^-133
+    const uint64_t full = (uint64_t(1) << 52) | mant;
+    const int sh = 942 - e;          // >= 46 here
+    if (sh > 54) return 0;
+    uint64_t r = full >> sh;
+    const uint64_t rem = full & ((uint64_t(1) << sh) - 1), half = uint64_t(1) << (sh - 1);
+    if (rem > half || (rem == half && (r & 1u))) ++r;
+    return uint16_t(r);
+}
+
 }  // namespace muw

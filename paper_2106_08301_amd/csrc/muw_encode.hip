@@ -314,31 +314,6 @@ __global__ __launch_bounds__(256) void k_directory(const TileCount *counts, Layo
     }
 }
 
-// fp64 -> bf16 bits, one rounding to nearest even, for finite q >= 0.
-__device__ inline uint16_t f64_to_bf16_rne(double q)
-{
-    const uint64_t b = uint64_t(__double_as_longlong(q));
-    const int e = int(b >> 52) & 0x7ff;
-    const uint64_t mant = b & ((uint64_t(1) << 52) - 1);
-    if (e == 0) return 0;            // zero or fp64 subnormal: far below half the smallest bf16
-    const int E = e - 1023 + 127;    // biased bf16 exponent
-    if (E >= 255) return 0x7f80;
-    if (E >= 1) {
-        uint32_t r = (uint32_t(E) << 7) | uint32_t(mant >> 45);
-        const uint64_t rem = mant & ((uint64_t(1) << 45) - 1), half = uint64_t(1) << 44;
-        if (rem > half || (rem == half && (r & 1u))) ++r;  // a carry runs into the exponent
-        return uint16_t(r);
-    }
-    // bf16 subnormal: multiples of 2^-133
-    const uint64_t full = (uint64_t(1) << 52) | mant;
-    const int sh = 942 - e;          // >= 46 here
-    if (sh > 54) return 0;
-    uint64_t r = full >> sh;
-    const uint64_t rem = full & ((uint64_t(1) << sh) - 1), half = uint64_t(1) << (sh - 1);
-    if (rem > half || (rem == half && (r & 1u))) ++r;
-    return uint16_t(r);
-}
-
 template <typename T>
 __device__ inline T bits_to_value(uint32_t bits)
 {
@@ -805,5 +780,23 @@ muw_status launch_decode(const muw_desc &d, const Layout &L, const void *blob, v
     MUW_DISPATCH_TB(decode_typed, L, blob, What, st);
     return hip_status(hipGetLastError());
 }
+
+// ---- the exact selection and the scan, for the other encoders of the library
+size_t select_workspace_bytes(int64_t NB)
+{
+    const uint64_t nchunks = (uint64_t(NB) + kChunk - 1) / kChunk;
+    return size_t(align16(sizeof(SelState)) + align16(nchunks * 4));
+}
+
+muw_status select_k_smallest(uint64_t *keys, int64_t NB, int64_t k, void *sel_ws, uint8_t *tags, uint8_t tag,
+                             uint64_t *other_keys, int poison, hipStream_t st)
+{
+    uint8_t *w = static_cast<uint8_t *>(sel_ws);
+    return select_smallest(keys, NB, k, reinterpret_cast<SelState *>(w),
+                           reinterpret_cast<uint32_t *>(w + align16(sizeof(SelState))), tags, tag, other_keys,
+                           poison, st);
+}
+
+void launch_exclusive_scan(uint32_t *v, int64_t n, hipStream_t st) { k_exclusive_scan<<<1, 256, 0, st>>>(v, n); }
 
 }  // namespace muw

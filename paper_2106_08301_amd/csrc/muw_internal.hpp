@@ -36,6 +36,13 @@ muw_status launch_admm_update(const muw_desc &d, const Layout &L, const void *W,
 muw_status launch_admm_penalty_grad(int64_t n, const void *W, const void *Q, const void *U, int dtype, float rho,
                                     float *G, hipStream_t st);
 
+// muw_encode.hip: exact "k smallest by (key, index)" over NB 64-bit keys (the selected blocks get `tag`; with
+// `poison` their entry in other_keys becomes all-ones), and an in-place exclusive prefix sum of n counters.
+size_t select_workspace_bytes(int64_t NB);
+muw_status select_k_smallest(uint64_t *keys, int64_t NB, int64_t k, void *sel_ws, uint8_t *tags, uint8_t tag,
+                             uint64_t *other_keys, int poison, hipStream_t st);
+void launch_exclusive_scan(uint32_t *v, int64_t n, hipStream_t st);
+
 struct GemmArgs {
     const void *blob;        // single problem
     const void *X;

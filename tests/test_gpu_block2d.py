@@ -1,0 +1,171 @@
+"""Layers encoded in two-dimensional [16, 32] blocks (Sec. 3.2, Table 1): HIP path versus the CPU oracle.
+
+Tags, stored magnitudes and the projected weights (hence every sign) must be bit-exact; GEMM outputs must
+satisfy relative Frobenius error <= 1e-3 and max abs error <= 1e-2 RMS(Y).  Sizes span several 256-column
+workgroup tiles, several 128-k slabs, more than one 64-block bitmap word, and ragged tails in M, N and K.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2106_08301_amd import synth
+from tests.gpu_util import check_close, to_device, to_f64
+
+pytestmark = pytest.mark.gpu
+
+BK, BN = 16, 32
+
+
+@pytest.fixture(scope="module")
+def muw():
+    from paper_2106_08301_amd import binding
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return binding
+
+
+def encode_both(muw, oracle, W, r_u, r_p):
+    Wd = W.f64()
+    N, K = Wd.shape
+    n_u, n_p = oracle.counts((N // BN) * (K // BK), r_u, r_p)
+    tags_o, mags_o, What = oracle.encode_2d(Wd, BK, BN, n_u, n_p, oracle.STORE_BF16)
+    layer = muw.muw_encode(to_device(W), BK, r_u, r_p, BN=BN)
+    assert (layer.desc.n_unified, layer.desc.n_pruned) == (n_u, n_p)
+    tags, signs, mags = muw.muw_export(layer)
+    assert signs is None
+    assert np.array_equal(tags.cpu().numpy(), tags_o)
+    assert np.array_equal(to_f64(mags), mags_o)
+    assert np.array_equal(to_f64(muw.muw_decode(layer)), What)
+    bits = oracle.counters_2d(tags_o.size, BK, BN, n_u, n_p, 16)[2]
+    assert layer.compressed_bytes == (bits + 7) // 8
+    return layer, What
+
+
+ENCODE_CASES = [
+    # N, K, r_u, r_p
+    (32, 16, 1.0, 0.0),            # a single block
+    (64, 64, 0.4, 0.5),
+    (96, 208, 0.5, 0.25),          # 13 block columns: ragged bitmap word, ragged slab
+    (288, 2064, 0.4, 0.5),         # 129 block columns: three bitmap words; 9 strips: two workgroup tiles along N
+    (64, 128, 0.0, 0.0),           # nothing constrained
+    (64, 128, 0.0, 1.0),           # everything pruned
+    (160, 1024, 0.3, 0.3),
+    (512, 4096, 0.7, 0.25),
+]
+
+
+@pytest.mark.parametrize("N,K,r_u,r_p", ENCODE_CASES)
+def test_encode_is_bit_exact(muw, oracle, N, K, r_u, r_p):
+    W = synth.normal_tensor(700 + N + K, (N, K), 0.02, "bf16", stream=1)
+    encode_both(muw, oracle, W, r_u, r_p)
+
+
+def test_encode_ties_and_signed_zeros(muw, oracle):
+    vals = np.zeros((128, 96))
+    vals[32:64, 16:32] = np.tile(np.array([0.5, -0.25, 0.0, -0.0]), (32, 4))
+    vals[64:96, :48] = np.tile(np.array([0.5, -0.25, 0.0, -0.0]), (32, 12))      # three equal blocks
+    vals[96:, 48:] = synth.standard_normal(8, 32 * 48).reshape(32, 48)
+    W = synth.from_values(vals, "bf16")
+    for r_u, r_p in [(0.5, 0.25), (0.25, 0.5), (1.0, 0.0)]:
+        encode_both(muw, oracle, W, r_u, r_p)
+
+
+GEMM_CASES = [
+    # N, K, r_u, r_p, Ms
+    (64, 64, 0.4, 0.5, [1, 5]),
+    (96, 208, 0.5, 0.25, [7, 32, 33]),
+    (288, 2064, 0.4, 0.5, [1, 64, 100, 129, 300]),
+    (160, 1024, 0.3, 0.3, [16, 200]),
+    (64, 128, 0.0, 0.0, [40]),
+    (512, 4096, 0.7, 0.25, [8, 256]),
+]
+
+
+@pytest.mark.parametrize("N,K,r_u,r_p,Ms", GEMM_CASES)
+def test_gemm_matches_oracle(muw, oracle, N, K, r_u, r_p, Ms):
+    W = synth.normal_tensor(800 + N + K, (N, K), 0.02, "bf16", stream=1)
+    layer, What = encode_both(muw, oracle, W, r_u, r_p)
+    for M in Ms:
+        X = synth.normal_tensor(900 + M, (M, K), 1.0, "bf16", stream=2)
+        Y = muw.muw_gemm(layer, to_device(X))
+        assert Y.dtype == torch.float32 and Y.shape == (M, N)
+        check_close(to_f64(Y), oracle.gemm(X.f64(), What))
+
+
+def test_gemm_all_pruned_is_exactly_zero(muw, oracle):
+    W = synth.normal_tensor(801, (64, 256), 0.02, "bf16", stream=1)
+    layer, What = encode_both(muw, oracle, W, 0.0, 1.0)
+    X = synth.normal_tensor(902, (70, 256), 1.0, "bf16", stream=2)
+    Y = torch.full((70, 64), 3.0, dtype=torch.float32, device="cuda")
+    muw.muw_gemm(layer, to_device(X), out=Y)
+    assert not Y.any()
+
+
+def test_gemm_strided_operands_and_bf16_output(muw, oracle):
+    N, K, M = 96, 272, 75
+    W = synth.normal_tensor(802, (N, K), 0.02, "bf16", stream=1)
+    layer, What = encode_both(muw, oracle, W, 0.5, 0.3)
+    X = synth.normal_tensor(903, (M, K), 1.0, "bf16", stream=2)
+    Y_ref = oracle.gemm(X.f64(), What)
+    big = torch.zeros((M, K + 24), dtype=torch.bfloat16, device="cuda")          # row stride K + 24 (a multiple of 8)
+    big[:, :K] = to_device(X)
+    out = torch.full((M, N + 5), 7.0, dtype=torch.float32, device="cuda")        # odd row stride: scalar stores
+    muw.muw_gemm(layer, big[:, :K], out=out[:, :N])
+    check_close(to_f64(out[:, :N]), Y_ref)
+    assert torch.all(out[:, N:] == 7.0)
+    Yb = muw.muw_gemm(layer, to_device(X), out_dtype=torch.bfloat16)
+    ref_b = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(Y_ref.astype(np.float32)))
+    check_close(to_f64(Yb), ref_b, rel=4e-3, mx=2e-2)
+    outb = torch.zeros((M, N + 3), dtype=torch.bfloat16, device="cuda")
+    muw.muw_gemm(layer, to_device(X), out=outb[:, :N])
+    assert torch.equal(outb[:, :N], Yb)
+
+
+def test_rejected_arguments(muw):
+    lib, dp = muw.lib, C.byref
+    blob, ws = C.c_size_t(), C.c_size_t()
+    d = muw.make_desc(48, 64, 16, muw.MUW_BF16, BN=32)                            # N % 32 != 0
+    assert lib.muw_encode_sizes(dp(d), 0.5, 0.2, dp(blob), dp(ws)) == muw.MUW_ESHAPE
+    d = muw.make_desc(64, 64, 16, muw.MUW_F32, BN=32)                             # fp32 storage
+    assert lib.muw_encode_sizes(dp(d), 0.5, 0.2, dp(blob), dp(ws)) == muw.MUW_EUNSUPPORTED
+    d = muw.make_desc(64, 64, 8, muw.MUW_BF16, BN=32)                             # only [16, 32]
+    assert lib.muw_encode_sizes(dp(d), 0.5, 0.2, dp(blob), dp(ws)) == muw.MUW_EUNSUPPORTED
+    d = muw.make_desc(64, 64, 16, muw.MUW_BF16, BN=16)
+    assert lib.muw_encode_sizes(dp(d), 0.5, 0.2, dp(blob), dp(ws)) == muw.MUW_EUNSUPPORTED
+    W = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    layer = muw.muw_encode(W, 16, 0.5, 0.25, BN=32)
+    sg = torch.zeros(8, dtype=torch.int16, device="cuda")
+    assert lib.muw_export(dp(layer.desc), layer.blob.data_ptr(), None, sg.data_ptr(), None, None) == muw.MUW_EINVAL
+    X = torch.zeros((4, 72), dtype=torch.bfloat16, device="cuda")
+    Y = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    # activation rows that are not 16-byte aligned (row stride 68)
+    Xo = torch.zeros((4, 68), dtype=torch.bfloat16, device="cuda")
+    assert lib.muw_gemm(dp(layer.desc), layer.blob.data_ptr(), Xo.data_ptr(), muw.MUW_BF16, 4, 68, Y.data_ptr(),
+                        muw.MUW_F32, 64, None, 0, None) == muw.MUW_EUNSUPPORTED
+    assert lib.muw_gemm(dp(layer.desc), layer.blob.data_ptr(), X.data_ptr(), muw.MUW_BF16, 4, 72, Y.data_ptr(),
+                        muw.MUW_F32, 64, None, 0, None) == muw.MUW_OK
+    assert lib.muw_conv2d(dp(layer.desc), layer.blob.data_ptr(), X.data_ptr(), muw.MUW_BF16, 1, 1, 1, 1, 0,
+                          Y.data_ptr(), muw.MUW_F32, None, 0, None) == muw.MUW_EUNSUPPORTED
+    Wn = W.clone()
+    Wn[3, 5] = float("nan")
+    with pytest.raises(muw.MuwError) as e:
+        muw.muw_encode(Wn, 16, 0.5, 0.25, BN=32)
+    assert e.value.status == muw.MUW_ENONFINITE
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_mlp_shapes_at_full_size(muw, oracle, which):
+    """The MLP GEMMs of the fifth benchmark configuration (4096 <-> 11008, 40 % unified, 50 % pruned) with
+    [16, 32] blocks, in the launch shape the benchmark times; sampled output rows against the oracle."""
+    case = synth.config5(2048, which)
+    X, W = synth.make_linear(case)
+    layer, What = encode_both(muw, oracle, W, case.r_unify, case.r_prune)
+    Xd = to_device(X)
+    Y = muw.muw_gemm(layer, Xd)
+    rows = [0, 1, 127, 128, 1000, 2047]
+    check_close(to_f64(Y[rows]), oracle.gemm(X.f64()[rows], What))
+    Y100 = muw.muw_gemm(layer, Xd[:100])
+    rows = [0, 31, 99]
+    check_close(to_f64(Y100[rows]), oracle.gemm(X.f64()[rows], What))
