@@ -16,9 +16,12 @@
 //        [dense bitmaps:   same shape, bit set = block DENSE]           (2 bits per block in all)
 //        [directory: (NS + 1) x {u32 first UNIFIED rank, u32 first DENSE rank} of each strip]
 //        [magnitudes: one bf16 per UNIFIED block, in block order]       (64-byte aligned)
-//        [sign planes: 64 bytes per UNIFIED block: plane i (i < 8, 64 bits) bit l = sign of the weight
-//         lane l holds at position i, i.e. W[32 s + l % 32][16 kc + 8 (l / 32) + i] < 0]
+//        [sign bytes: 64 bytes per UNIFIED block, byte l = the signs of the 8 weights lane l holds,
+//         W[32 s + l % 32][16 kc + 8 (l / 32) + i], i < 8: bit i / 2 for even i, bit 4 + i / 2 for odd i, so
+//         that t = byte | byte << 12 has the signs of weights (2 d, 2 d + 1) 16 bits apart and one shift by
+//         15 - d puts them on bits 15 and 31 of output register d]
 //        [dense payload: 1024 bytes per DENSE block, lane l's 8 values at byte 16 l]
+//        [1 KiB of slack: the GEMM fetches magnitudes and sign bytes in whole groups of 8 blocks]
 // A strip's payload is contiguous and in kc order, so a wavefront walks it with two running counters.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -58,7 +61,7 @@ __host__ __device__ inline Layout2 make_layout2(int64_t N, int64_t K, int64_t n_
     L.mags_off = align64(L.dir_off + uint64_t(L.NS + 1) * 8u);
     L.signs_off = align64(L.mags_off + uint64_t(n_u) * 2u);
     L.dense_off = L.signs_off + uint64_t(n_u) * 64u;
-    L.total = align64(L.dense_off + uint64_t(n_d) * 1024u);
+    L.total = align64(L.dense_off + uint64_t(n_d) * 1024u) + 1024u;
     return L;
 }
 

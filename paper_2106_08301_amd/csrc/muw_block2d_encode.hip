@@ -152,17 +152,16 @@ __global__ __launch_bounds__(256) void k_pack2d(const uint16_t *W, const uint8_t
     }
     const uint64_t g = uint64_t(cnt_u[s]) + rank[j];
     const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
-    uint64_t mine = 0;
+    uint32_t byte = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const uint32_t bits = (v[i >> 1] >> ((i & 1) * 16)) & 0xffffu;
         // Eq. 2: w >= 0 (which includes -0.0) maps to +q
         const bool neg = (bits & 0x8000u) && (bits & 0x7fffu);
-        const uint64_t plane = __ballot(neg);
-        if (lane == i) mine = plane;
+        if (neg) byte |= 1u << ((i >> 1) + 4 * (i & 1));
     }
-    if (lane < 8) reinterpret_cast<uint64_t *>(blob + L.signs_off + g * 64u)[lane] = mine;
-    if (lane == 8) reinterpret_cast<uint16_t *>(blob + L.mags_off)[g] = f64_to_bf16_rne(q[j]);
+    (blob + L.signs_off + g * 64u)[lane] = uint8_t(byte);
+    if (lane == 0) reinterpret_cast<uint16_t *>(blob + L.mags_off)[g] = f64_to_bf16_rne(q[j]);
 }
 
 // Tag and payload rank of block (s, kc) from the bitmaps.
@@ -216,12 +215,12 @@ __global__ __launch_bounds__(256) void k_decode2d(const uint8_t *blob, Layout2 L
         out = *reinterpret_cast<const uint4 *>(blob + L.dense_off + r.rank * 1024u + uint32_t(lane) * 16u);
     } else if (r.tag == MUW_TAG_UNIFIED) {
         const uint32_t q = reinterpret_cast<const uint16_t *>(blob + L.mags_off)[r.rank];
-        const uint64_t *planes = reinterpret_cast<const uint64_t *>(blob + L.signs_off + r.rank * 64u);
+        const uint32_t byte = (blob + L.signs_off + r.rank * 64u)[lane];
         uint32_t v[4];
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-            const uint32_t lo = q | (uint32_t((planes[2 * d] >> lane) & 1) << 15);
-            const uint32_t hi = q | (uint32_t((planes[2 * d + 1] >> lane) & 1) << 15);
+            const uint32_t lo = q | (((byte >> d) & 1u) << 15);
+            const uint32_t hi = q | (((byte >> (d + 4)) & 1u) << 15);
             v[d] = lo | (hi << 16);
         }
         out = make_uint4(v[0], v[1], v[2], v[3]);

@@ -7,11 +7,10 @@
 //     sides; its 16-byte chunks are stored XOR-swizzled with the row number so that the 64 lanes of a
 //     fragment read (32 rows x 2 chunks) hit distinct banks.
 //   - A wavefront walks the present-bitmap of its strip: a PRUNED block costs nothing at all -- no bytes,
-//     no decode, no MFMA (Sec. 3.2: pruned blocks are skipped).  A UNIFIED block arrives through the scalar
-//     cache (magnitude + 8 sign planes of 64 bits = 16 scalar registers): plane i IS the lane mask "the
-//     lane's i-th weight is negative", so the decode is two selects and one merge per register.  A DENSE
-//     block is one 16-byte vector load per lane.  The next block's payload is requested before the
-//     current block's MFMAs are issued.
+//     no decode, no MFMA (Sec. 3.2: pruned blocks are skipped).  The payload of UNIFIED blocks (a magnitude
+//     and one sign byte per lane) also comes through LDS by global_load_lds, a slab ahead of its use; the
+//     decode is one shift and one bit-select per operand register.  A DENSE block is one 16-byte vector
+//     load per lane.
 //   - Per surviving block and 32 activation rows: one ds_read_b128 and one v_mfma_f32_32x32x16_bf16 with
 //     the weights as the A operand, so that a lane ends up with 4 consecutive output columns per register
 //     quad and the epilogue writes 16 bytes per lane.
@@ -47,6 +46,14 @@ struct B2Args {
     int32_t ydtype, vec_store;
 };
 
+// (x & mask) | y in one instruction
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t y)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(y));
+    return r;
+}
+
 template <int OFF>
 __device__ inline u32x4 lds_read_b128_at(uint32_t addr)
 {
@@ -56,11 +63,12 @@ __device__ inline u32x4 lds_read_b128_at(uint32_t addr)
 }
 
 template <int MSUB>
-__global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_block2d_gemm_bf16(B2Args a)
 {
     constexpr int MT = 32 * MSUB;
     constexpr uint32_t kSlabBytes = uint32_t(MT) * kSlabK * 2u;
-    __shared__ __attribute__((aligned(1024))) uint8_t xs[2 * kSlabBytes];
+    constexpr uint32_t kRingBytes = 3u * 512u + 64u;  // per wave: three groups of sign bytes and of magnitudes
+    __shared__ __attribute__((aligned(1024))) uint8_t xs[2 * kSlabBytes + kWaves * kRingBytes];
 
     // Consecutive workgroup ids go to consecutive XCDs; give each XCD a contiguous run of the M-major tile
     // list, so the workgroups resident on one XCD share their activation rows in its L2.
@@ -79,12 +87,11 @@ __global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
     // ---- activation slabs: DMA instruction i of this wave fills rows (8 i + wave) * 4 .. + 3 of the tile
     const uint32_t sub = uint32_t(lane) >> 4, pos = uint32_t(lane) & 15u;       // row inside the 4, chunk position
     const uint32_t swz = pos ^ ((wave * 4u + sub) & 15u);                        // chunk of the row stored at `pos`
-    const uint16_t *xrow[MSUB];
+    uint32_t xrow[MSUB];
 #pragma unroll
     for (int i = 0; i < MSUB; ++i) {
-        uint32_t row = m0 + (uint32_t(i) * 8u + wave) * 4u + sub;
-        if (row >= uint32_t(a.M)) row = uint32_t(a.M) - 1u;
-        xrow[i] = a.X + int64_t(row) * a.ldx;
+        xrow[i] = m0 + (uint32_t(i) * 8u + wave) * 4u + sub;
+        if (xrow[i] >= uint32_t(a.M)) xrow[i] = uint32_t(a.M) - 1u;
     }
     auto issue_slab = [&](uint32_t j) __attribute__((always_inline)) {
         uint32_t k = j * kSlabK + swz * 8u;
@@ -92,7 +99,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
         uint8_t *dst = xs + (j & 1u) * kSlabBytes + wave * 1024u;
 #pragma unroll
         for (int i = 0; i < MSUB; ++i)
-            __builtin_amdgcn_global_load_lds((global_void *)(xrow[i] + k), (lds_void *)(dst + i * 8192), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_void *)(a.X + (uint64_t(xrow[i]) * uint64_t(a.ldx) + k)),
+                                             (lds_void *)(dst + i * 8192), 16, 0, 0);
     };
 
     // ---- fragment reads: lane (m = lane % 32, h = lane / 32) wants chunk 2 kc + h of row 32 mt + m
@@ -100,55 +108,40 @@ __global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
     const uint32_t frag_base = lds_base + (uint32_t(lane) & 31u) * 256u;
     const uint32_t frag_swz = (uint32_t(lane) >> 5) ^ (uint32_t(lane) & 15u);
 
-    // ---- the strip's blocks
+    // ---- the strip's payload.  Magnitudes and sign bytes of UNIFIED blocks are fetched in groups of 8
+    // consecutive blocks (group Q = payload ranks 8 Q .. 8 Q + 7: 16 + 512 bytes) into a per-wave ring of three
+    // groups.  Right after a slab barrier the wave requests the groups that hold the next 24 ranks; a slab uses
+    // at most 8, and the wait before the next barrier covers the requests: a rank is in the ring at least one
+    // slab before it can be needed, and no wait is ever spent on it alone.
     c_u64 *present = (c_u64 *)(a.blob + a.present_off) + uint64_t(strip) * a.W64;
     c_u64 *densemap = (c_u64 *)(a.blob + a.densemap_off) + uint64_t(strip) * a.W64;
-    c_u32 *mags32 = (c_u32 *)(a.blob + a.mags_off);
-    uint32_t g = 0, ru = 0, rd = 0;
-    uint64_t pm = 0, dm = 0;
+    const uint32_t ring_lds = lds_base + 2u * kSlabBytes + wave * kRingBytes;  // [3][512] sign bytes, [3][16] magnitudes
+    uint8_t *ring_ptr = xs + 2u * kSlabBytes + wave * kRingBytes;
+    const uint32_t sign_lane = ring_lds + uint32_t(lane);
+    const uint64_t sign_src = reinterpret_cast<uint64_t>(a.blob) + a.signs_off + uint32_t(lane & 31) * 16u;
+    const uint64_t mag_src = reinterpret_cast<uint64_t>(a.blob) + a.mags_off;
+    const uint8_t *dense_lane = a.blob + a.dense_off + uint32_t(lane) * 16u;
+
+    uint32_t ru = 0, rd = 0, ru_stop = 0;  // next UNIFIED / DENSE rank of the strip, end of its UNIFIED ranks
     if (live) {
         c_u32 *dir = (c_u32 *)(a.blob + a.dir_off) + 2u * strip;
         ru = dir[0];
         rd = dir[1];
-        pm = present[0];
-        dm = densemap[0];
+        ru_stop = dir[2];
     }
-    // Two register sets take turns: while the MFMAs of the block in one set run, the payload of the strip's
-    // next block is on its way into the other (scalar loads for a UNIFIED block, one vector load per lane for
-    // a DENSE one).  The walk is one loop over the strip's surviving blocks; whenever the next block lies in a
-    // later slab the wave first passes the barriers in between, so every wave passes nslabs barriers in all.
-    constexpr uint32_t kNone = 0x7fffffffu;
-    struct Blk {
-        uint32_t kc, qword, qshift;
-        bool dense;
-        uint64_t plane[8];
-        u32x4 raw;
-    };
-    const uint8_t *dense_lane = a.blob + a.dense_off + uint32_t(lane) * 16u;
-    auto fetch = [&](Blk &n) __attribute__((always_inline)) {
-        while (pm == 0 && g + 1 < a.W64 && live) {
-            ++g;
-            pm = present[g];
-            dm = densemap[g];
-        }
-        if (pm == 0) {
-            n.kc = kNone;
-            return;
-        }
-        const uint32_t b = uint32_t(__builtin_ctzll(pm));
-        pm &= pm - 1;
-        n.kc = g * 64u + b;
-        n.dense = (dm >> b) & 1u;
-        if (n.dense) {
-            n.raw = *reinterpret_cast<const u32x4 *>(dense_lane + uint64_t(rd) * 1024u);
-            ++rd;
-        } else {
-            c_u64 *pl = (c_u64 *)(a.blob + a.signs_off + uint64_t(ru) * 64u);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) n.plane[i] = pl[i];
-            n.qword = mags32[ru >> 1];
-            n.qshift = (ru & 1u) * 16u;
-            ++ru;
+    uint32_t q_next = ru >> 3, q_slot = q_next % 3u;  // next group to request, its ring slot
+    uint32_t rslot = ru % 24u;                        // ring position of rank ru
+    auto request_groups = [&]() __attribute__((always_inline)) {
+        // (group q_next replaces group q_next - 3, whose last rank 8 q_next - 17 is below ru)
+        while (q_next * 8u <= ru + 16u && q_next * 8u < ru_stop) {
+            if (lane < 32)
+                __builtin_amdgcn_global_load_lds((global_void *)(sign_src + uint64_t(q_next) * 512u),
+                                                 (lds_void *)(ring_ptr + q_slot * 512u), 16, 0, 0);
+            if (lane == 0)
+                __builtin_amdgcn_global_load_lds((global_void *)(mag_src + uint64_t(q_next) * 16u),
+                                                 (lds_void *)(ring_ptr + 1536u + q_slot * 16u), 16, 0, 0);
+            ++q_next;
+            q_slot = q_slot == 2u ? 0u : q_slot + 1u;
         }
     };
 
@@ -158,57 +151,70 @@ __global__ __launch_bounds__(kWaves * 64) void k_block2d_gemm_bf16(B2Args a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
-    // slab `have` is the one the workgroup may read (-1: none yet)
-    int32_t have = -1;
-    auto next_slab = [&]() __attribute__((always_inline)) {
-        ++have;
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of slab `have` has landed
-        __syncthreads();                     // ... and everybody's; everybody is done with the slab before it
-        if (uint32_t(have) + 1u < nslabs) issue_slab(uint32_t(have) + 1u);
-    };
-    auto step = [&](Blk &c, Blk &n) __attribute__((always_inline)) {
-        while (have < int32_t(c.kc >> 3)) next_slab();
-        const uint32_t addr = frag_base + (uint32_t(have) & 1u) * kSlabBytes + ((((c.kc & 7u) * 2u) ^ frag_swz) << 4);
-        u32x4 xf[MSUB];
-        if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
-        if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
-        if constexpr (MSUB >= 4) {
-            xf[2] = lds_read_b128_at<16384>(addr);
-            xf[3] = lds_read_b128_at<24576>(addr);
-        }
-        u32x4 wf;
-        if (c.dense) {
-            wf = c.raw;
-        } else {
-            const uint32_t q = (c.qword >> c.qshift) & 0xffffu;
-            const uint32_t qq = q | (q << 16), qn = qq ^ 0x80008000u;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const uint32_t lo = __builtin_amdgcn_inverse_ballot_w64(c.plane[2 * d]) ? qn : qq;
-                const uint32_t hi = __builtin_amdgcn_inverse_ballot_w64(c.plane[2 * d + 1]) ? qn : qq;
-                wf[d] = (lo & 0xffffu) | (hi & 0xffff0000u);
-            }
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xf[0]));
-#pragma unroll
-        for (int i = 1; i < MSUB; ++i) asm volatile("" : "+v"(xf[i]));
-        fetch(n);
-#pragma unroll
-        for (int i = 0; i < MSUB; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf),
-                                                             __builtin_bit_cast(bf16x8, xf[i]), acc[i], 0, 0, 0);
-    };
-
+    uint64_t pw = 0, dw = 0;
     issue_slab(0);
-    Blk A, B;
-    fetch(A);
-    for (;;) {
-        if (A.kc == kNone) break;
-        step(A, B);
-        if (B.kc == kNone) break;
-        step(B, A);
+    request_groups();
+#pragma unroll 1
+    for (uint32_t step = 0; step < nslabs; ++step) {
+        // this wave's requests (slab `step`, payload groups) have landed, everybody's have, and everybody is done
+        // with the slab before this one (its LDS reads were waited for before its MFMAs)
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        if (step + 1u < nslabs) issue_slab(step + 1u);
+        request_groups();
+
+        // the 8 blocks of this slab: bits 8 (step % 8) .. + 7 of the strip's bitmap words
+        if ((step & 7u) == 0 && live) {
+            pw = present[step >> 3];
+            dw = densemap[step >> 3];
+        }
+        uint32_t p8 = uint32_t(pw >> ((step & 7u) * 8u)) & 0xffu;
+        const uint32_t d8 = uint32_t(dw >> ((step & 7u) * 8u)) & 0xffu;
+        const uint32_t slab_addr = frag_base + (step & 1u) * kSlabBytes;
+        while (p8 != 0) {
+            const uint32_t b = uint32_t(__builtin_ctz(p8));
+            p8 &= p8 - 1;
+            const uint32_t addr = slab_addr + (((b * 2u) ^ frag_swz) << 4);
+            u32x4 xf[MSUB];
+            if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
+            if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
+            if constexpr (MSUB >= 4) {
+                xf[2] = lds_read_b128_at<16384>(addr);
+                xf[3] = lds_read_b128_at<24576>(addr);
+            }
+            u32x4 wf;
+            if ((d8 >> b) & 1u) {
+                // (a DENSE block is fetched when it is met; its wait also covers the slab in flight)
+                const uint8_t *src = dense_lane + uint64_t(rd) * 1024u;
+                asm volatile("global_load_dwordx4 %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(wf) : "v"(src) : "memory");
+                ++rd;
+            } else {
+                uint32_t sb, mg;
+                asm volatile("ds_read_u8 %0, %2\n\tds_read_u16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(sb), "=&v"(mg)
+                             : "v"(sign_lane + rslot * 64u), "v"(ring_lds + 1536u + rslot * 2u)
+                             : "memory");
+                ++ru;
+                rslot = rslot == 23u ? 0u : rslot + 1u;
+                const uint32_t qq = mg | (mg << 16);
+                const uint32_t t = sb | (sb << 12);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) wf[d] = and_or(t << (15 - d), 0x80008000u, qq);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xf[0]));
+#pragma unroll
+            for (int i = 1; i < MSUB; ++i) asm volatile("" : "+v"(xf[i]));
+            // (inline assembly keeps every accumulator in place; two idle cycles between the last write of the
+            // weight operand and its first use)
+            asm volatile("s_nop 1" : "+v"(wf));
+#pragma unroll
+            for (int i = 0; i < MSUB; ++i)
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(wf), "v"(xf[i]));
+        }
     }
-    while (have + 1 < int32_t(nslabs)) next_slab();  // the barriers of the slabs after the strip's last block
+    // the accumulators were written by inline assembly: let the last MFMA drain before they are read
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < MSUB; ++i) asm volatile("" : "+v"(acc[i]));
 
     // ---- epilogue: lane (m = lane % 32, h = lane / 32) holds columns 8 b + 4 h .. + 3 of its row in
     // registers 4 b .. 4 b + 3 of each accumulator
