@@ -175,24 +175,32 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
             p8 &= p8 - 1;
             const uint32_t addr = slab_addr + (((b * 2u) ^ frag_swz) << 4);
             u32x4 xf[MSUB];
-            if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
-            if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
-            if constexpr (MSUB >= 4) {
-                xf[2] = lds_read_b128_at<16384>(addr);
-                xf[3] = lds_read_b128_at<24576>(addr);
-            }
+            auto read_fragments = [&]() __attribute__((always_inline)) {
+                if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
+                if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
+                if constexpr (MSUB >= 4) {
+                    xf[2] = lds_read_b128_at<16384>(addr);
+                    xf[3] = lds_read_b128_at<24576>(addr);
+                }
+            };
             u32x4 wf;
             if ((d8 >> b) & 1u) {
+                read_fragments();
                 // (a DENSE block is fetched when it is met; its wait also covers the slab in flight)
                 const uint8_t *src = dense_lane + uint64_t(rd) * 1024u;
                 asm volatile("global_load_dwordx4 %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(wf) : "v"(src) : "memory");
                 ++rd;
             } else {
+                // payload first: LDS reads return in order, so the decode runs while the fragments arrive
                 uint32_t sb, mg;
-                asm volatile("ds_read_u8 %0, %2\n\tds_read_u16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                asm volatile("ds_read_u8 %0, %2\n\tds_read_u16 %1, %3"
                              : "=&v"(sb), "=&v"(mg)
                              : "v"(sign_lane + rslot * 64u), "v"(ring_lds + 1536u + rslot * 2u)
                              : "memory");
+                read_fragments();
+                if constexpr (MSUB == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(sb), "+v"(mg));
+                if constexpr (MSUB == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(sb), "+v"(mg));
+                if constexpr (MSUB == 4) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(sb), "+v"(mg));
                 ++ru;
                 rslot = rslot == 23u ? 0u : rslot + 1u;
                 const uint32_t qq = mg | (mg << 16);
@@ -292,9 +300,13 @@ muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X
     a.ydtype = ydtype;
     const uint32_t ybytes = ydtype == MUW_F32 ? 4u : 2u;
     a.vec_store = ((reinterpret_cast<uintptr_t>(Y) & (4u * ybytes - 1u)) == 0 && (ldy & 3) == 0) ? 1 : 0;
-    if (M <= 32) return launch<1>(a, 1, st);
-    if (M <= 64) return launch<2>(a, 1, st);
-    return launch<4>(a, uint32_t((M + 127) / 128), st);
+    // Rows per workgroup: 128 when that still gives every compute unit a workgroup, else 64 or 32 (more,
+    // smaller workgroups; each re-reads the compressed weights, which is the cheap operand here).
+    const uint64_t full = 256;
+    if (M > 64 && uint64_t((M + 127) / 128) * a.n_ntiles >= full) return launch<4>(a, uint32_t((M + 127) / 128), st);
+    if (M > 32 && uint64_t((M + 63) / 64) * a.n_ntiles >= full) return launch<2>(a, uint32_t((M + 63) / 64), st);
+    if (M > 128) return launch<4>(a, uint32_t((M + 127) / 128), st);
+    return launch<1>(a, uint32_t((M + 31) / 32), st);
 }
 
 }  // namespace muw
