@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the unified/pruned-weight GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg5] [--report]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg5|cfg5_block2d] [--report]
 
 Headline workload (config.workload = "cfg4_decode_projections"): the transformer projection GEMMs of
 the decode regime -- K = N = 4096, blocks of 16 along K, 70 % unified / 25 % pruned / 5 % dense, bf16,
@@ -13,6 +13,10 @@ inputs are resident in HBM before the timed region.  `value` is compressed-weigh
 The line printed on stdout is one JSON object; `roofline` describes the streaming kernel (algorithmic
 bytes = compressed weights + activations + outputs per launch, against the 8 TB/s HBM peak) and
 `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+
+--workload cfg5 times the MLP GEMMs (4096 <-> 11008, M = 2048, 40 % unified / 50 % pruned) with blocks of 8
+along K; --workload cfg5_block2d the same shapes and ratios with the two-dimensional [16, 32] blocks, where a
+pruned block removes whole matrix instructions.
 """
 import argparse
 import json
@@ -40,7 +44,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps first (the GPU takes tens of milliseconds of load to reach its clocks)")
-    ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg5", "copy"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg5", "cfg5_block2d", "copy"])
     ap.add_argument("--groups", type=int, default=128, help="distinct encoded matrices per launch (cfg4)")
     ap.add_argument("--distinct", type=int, default=4, help="matrices generated from distinct seeds (cfg4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -167,27 +171,41 @@ def bench_cfg4(args, torch, muw, synth, to_device):
     return out
 
 
-def bench_cfg5(args, torch, muw, synth, to_device):
+def bench_cfg5(args, torch, muw, synth, to_device, block2d=False):
+    """The two MLP GEMMs at M = 2048, one launch each per step.  block2d: [16, 32] blocks instead of [8, 1];
+    executed flops are then the surviving ones (pruned blocks are skipped outright)."""
     res = {}
     total_flops_surv, total_ms = 0.0, 0.0
     for which in ("up", "down"):
         case = synth.config5(2048, which)
         X, W = synth.make_linear(case)
-        layer = muw.muw_encode(to_device(W), case.B, case.r_unify, case.r_prune)
+        if block2d:
+            layer = muw.muw_encode(to_device(W), 16, case.r_unify, case.r_prune, BN=32)
+            per_block = 16 * 32
+        else:
+            layer = muw.muw_encode(to_device(W), case.B, case.r_unify, case.r_prune)
+            per_block = case.B
         Xd = to_device(X)
         Y = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
         _, ms = time_steps(torch, lambda: muw.muw_gemm(layer, Xd, out=Y), args.steps, args.warmup)
-        surv = 2.0 * case.M * case.B * (layer.NB - layer.desc.n_pruned)
+        surv = 2.0 * case.M * per_block * (layer.NB - layer.desc.n_pruned)
         dense = 2.0 * case.M * case.N * case.K
-        res[which] = {"ms": ms, "surviving_TFLOPs": surv / ms / 1e9, "executed_dense_TFLOPs": dense / ms / 1e9}
+        # executed: what the matrix cores are given -- everything for [8, 1] blocks (a 16-row operand tile is
+        # never pruned as a whole), the surviving blocks only for [16, 32] blocks
+        res[which] = {"ms": ms, "surviving_TFLOPs": surv / ms / 1e9,
+                      "executed_dense_TFLOPs": (surv if block2d else dense) / ms / 1e9,
+                      "dense_equivalent_TFLOPs": dense / ms / 1e9, "compressed_bytes": layer.compressed_bytes}
         total_flops_surv += surv
         total_ms += ms
+    name = "cfg5_mlp_M2048_blocks16x32" if block2d else "cfg5_mlp_M2048"
+    kernel = "k_block2d_gemm_bf16" if block2d else "k_pipe_gemm_bf16"
     return {"metric": "dense-equivalent TFLOP/s on surviving blocks (M=2048 MLP GEMMs)",
             "value": total_flops_surv / total_ms / 1e9, "unit": "TFLOP/s", "ms_per_step": total_ms,
-            "config": {"workload": "cfg5_mlp_M2048"}, "per_gemm": res,
-            "roofline": {"bound": "mfma", "achieved": total_flops_surv / total_ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": total_flops_surv / total_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                         "traffic": traffic_from_profiles("k_pipe_gemm_bf16_cfg5")}}
+            "config": {"workload": name, "block_shape": [16, 32] if block2d else [8, 1]}, "per_gemm": res,
+            "roofline": {"kernel": kernel, "bound": "mfma", "achieved": total_flops_surv / total_ms / 1e9,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": total_flops_surv / total_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": traffic_from_profiles(kernel + "_cfg5")}}
 
 
 def _roof(bytes_algo, flops_surv, ms):
@@ -261,6 +279,21 @@ def report_all(args, torch, muw, synth, to_device):
     for which in ("up", "down"):
         for M in (128, 2048):
             linear_row(f"cfg5 mlp {which} B8 M={M}", synth.config5(M, which), M)
+    for which in ("up", "down"):
+        for M in (128, 2048):
+            case = synth.config5(M, which)
+            X, W = synth.make_linear(case, M=M)
+            Xd, Wd = to_device(X), to_device(W)
+            layer = muw.muw_encode(Wd, 16, case.r_unify, case.r_prune, BN=32)
+            Y = torch.empty((M, case.N), dtype=torch.float32, device="cuda")
+            _, ms = time_steps(torch, lambda: muw.muw_gemm(layer, Xd, out=Y), 20, 5)
+            _, ms_torch = time_steps(torch, lambda: torch.matmul(Xd, Wd.T), 10, 2)
+            b = layer.compressed_bytes + M * case.K * 2 + M * case.N * 4
+            surv = 2.0 * M * 512 * (layer.NB - layer.desc.n_pruned)
+            rows.append({"config": f"cfg5 mlp {which} blocks [16,32] M={M}", "ms": ms, "algorithmic_GBps": b / ms / 1e6,
+                         "compressed_weight_GBps": layer.compressed_bytes / ms / 1e6,
+                         "surviving_TFLOPs": surv / ms / 1e9, "executed_dense_TFLOPs": surv / ms / 1e9,
+                         "roofline_frac": _roof(b, surv, ms), "ms_torch_dense": ms_torch})
     log(f"{'config':62s} {'ms':>9s} {'GB/s':>8s} {'TF surv':>8s} {'TF exec':>8s} {'roof':>6s} {'torch ms':>9s}")
     for r in rows:
         log(f"{r['config']:62s} {r['ms']:9.4f} {r['algorithmic_GBps']:8.0f} {r.get('surviving_TFLOPs', 0):8.1f} "
@@ -299,7 +332,7 @@ def main():
     if args.workload == "cfg4":
         out = bench_cfg4(args, torch, muw, synth, to_device)
     else:
-        out = bench_cfg5(args, torch, muw, synth, to_device)
+        out = bench_cfg5(args, torch, muw, synth, to_device, block2d=args.workload == "cfg5_block2d")
     line = {"metric": out.pop("metric"), "value": out.pop("value"), "unit": out.pop("unit"), "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": out.pop("ms_per_step"),
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
