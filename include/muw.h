@@ -129,6 +129,20 @@ muw_status muw_admm_update(const muw_desc *desc, const void *W_dev, void *U_dev,
 muw_status muw_admm_penalty_grad(int64_t count, const void *W_dev, const void *Q_dev, const void *U_dev,
                                  muw_dtype dtype, float rho, float *G_dev, void *hip_stream);
 
+/* Unify() for a free two-dimensional block shape [BK, BN] (Sec. 3.2, Table 1: BK weights along the contraction
+ * direction K, BN along the output rows N; [2,2], [4,1], [8,1] are the paper's own examples), written out dense:
+ * the Q-step of Alg. 1 and the one-shot compression of Sec. 4.3 for shapes that have no packed format here.
+ * Block j = (n / BN) * (K / BK) + k / BK; q = mean |w| over the block; the scores e_p = sum w^2 and
+ * e_u = sum (|w| - q)^2 are summed in fp64 row by row, k ascending inside a row; selection and rounding as in
+ * muw_encode (n_p smallest (e_p, j) PRUNED first, then n_u smallest (e_u, j) UNIFIED, counts by muw_counts).
+ * W_dev: [N][K] row-major of `dtype`.  Outputs, each optional (NULL): tags_dev[NB] (muw_tag), mags_dev[NB]
+ * (`dtype`; 0 unless UNIFIED), What_dev[N][K] (`dtype`: +-q^, 0, or the weight itself).  N % BN == 0, K % BK == 0,
+ * BK * BN <= 4096.  Waits for the stream before returning; MUW_ENONFINITE on NaN/Inf weights. */
+size_t muw_unify_workspace_bytes(int64_t N, int64_t K, int32_t BK, int32_t BN);
+muw_status muw_unify(int64_t N, int64_t K, int32_t BK, int32_t BN, const void *W_dev, muw_dtype dtype,
+                     double r_unify, double r_prune, uint8_t *tags_dev, void *mags_dev, void *What_dev,
+                     void *ws_dev, size_t ws_bytes, void *hip_stream);
+
 /* Layout-independent view of an encoded layer, for bit-exact comparison: tags_dev[NB] (muw_tag),
  * signs_dev[NB] (bit l = w_l < 0; 0 unless UNIFIED), mags_dev[NB] (stored magnitude in wdtype; 0 unless
  * UNIFIED).  Any of the three may be NULL. */

@@ -20,7 +20,7 @@ MUW_LAYOUT_NK, MUW_LAYOUT_OIHW = 0, 1
 EXPORTED = ["muw_version", "muw_status_str", "muw_counts", "muw_encode_sizes", "muw_encode", "muw_export",
             "muw_decode", "muw_compressed_bytes", "muw_gemm_workspace_bytes", "muw_gemm",
             "muw_gemm_grouped", "muw_conv2d_workspace_bytes", "muw_conv2d", "muw_admm_workspace_bytes",
-            "muw_admm_update", "muw_admm_penalty_grad"]
+            "muw_admm_update", "muw_admm_penalty_grad", "muw_unify_workspace_bytes", "muw_unify"]
 
 
 class muw_desc(C.Structure):
@@ -63,6 +63,10 @@ def _load():
     L.muw_admm_workspace_bytes.restype = sz
     L.muw_admm_update.argtypes = [dp, vp, vp, vp, C.c_int, dbl, dbl, vp, sz, vp]
     L.muw_admm_penalty_grad.argtypes = [i64, vp, vp, vp, C.c_int, C.c_float, vp, vp]
+    L.muw_unify_workspace_bytes.argtypes = [i64, i64, i32, i32]
+    L.muw_unify_workspace_bytes.restype = sz
+    L.muw_unify.argtypes = [i64, i64, i32, i32, vp, C.c_int, dbl, dbl, vp, vp, vp, vp, sz, vp]
+    L.muw_unify.restype = C.c_int
     for name in ("muw_counts", "muw_encode_sizes", "muw_encode", "muw_export", "muw_decode", "muw_gemm",
                  "muw_gemm_grouped", "muw_conv2d", "muw_admm_update", "muw_admm_penalty_grad"):
         getattr(L, name).restype = C.c_int
@@ -188,6 +192,23 @@ def muw_admm_penalty_grad(W, Q, U, rho):
     _check(lib.muw_admm_penalty_grad(W.numel(), _ptr(W), _ptr(Q), _ptr(U), _dtype_code(W), float(rho), _ptr(G),
                                      _stream()), "muw_admm_penalty_grad")
     return G
+
+
+def muw_unify(W, BK, BN, r_unify, r_prune):
+    """Unify() for [BK, BN] blocks of a 2-D weight tensor.  Returns (tags u8[NB], mags [NB], What [N, K])."""
+    assert W.is_cuda and W.is_contiguous() and W.dim() == 2
+    N, K = W.shape
+    ws_bytes = lib.muw_unify_workspace_bytes(N, K, BK, BN)
+    if ws_bytes == 0:
+        raise MuwError(MUW_ESHAPE, "muw_unify")
+    NB = (N // BN) * (K // BK)
+    tags = torch.empty(NB, dtype=torch.uint8, device=W.device)
+    mags = torch.empty(NB, dtype=W.dtype, device=W.device)
+    What = torch.empty_like(W)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=W.device)
+    _check(lib.muw_unify(N, K, BK, BN, _ptr(W), _dtype_code(W), r_unify, r_prune, _ptr(tags), _ptr(mags), _ptr(What),
+                         _ptr(ws), ws_bytes, _stream()), "muw_unify")
+    return tags, mags, What
 
 
 def muw_export(layer):

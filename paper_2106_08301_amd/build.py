@@ -19,7 +19,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-PER_FILE = {"muw_encode.hip": ["-ffp-contract=off"], "muw_block2d_encode.hip": ["-ffp-contract=off"]}
+PER_FILE = {"muw_encode.hip": ["-ffp-contract=off"], "muw_block2d_encode.hip": ["-ffp-contract=off"],
+            "muw_unify.hip": ["-ffp-contract=off"]}
 EXTRA = os.environ.get("MUW_EXTRA_HIPCC_FLAGS", "").split()  # e.g. -DMUW_STREAM_WAVES=4 for experiments
 
 

@@ -196,6 +196,33 @@ muw_status muw_admm_penalty_grad(int64_t count, const void *W_dev, const void *Q
                                     static_cast<hipStream_t>(hip_stream));
 }
 
+size_t muw_unify_workspace_bytes(int64_t N, int64_t K, int32_t BK, int32_t BN)
+{
+    if (N <= 0 || K <= 0 || BK <= 0 || BN <= 0 || K % BK != 0 || N % BN != 0) return 0;
+    return unify_workspace_bytes((N / BN) * (K / BK));
+}
+
+muw_status muw_unify(int64_t N, int64_t K, int32_t BK, int32_t BN, const void *W_dev, muw_dtype dtype, double r_unify,
+                     double r_prune, uint8_t *tags_dev, void *mags_dev, void *What_dev, void *ws_dev, size_t ws_bytes,
+                     void *hip_stream)
+{
+    if (N <= 0 || K <= 0 || BK <= 0 || BN <= 0 || !valid_dtype(dtype)) return MUW_EINVAL;
+    if (K % BK != 0 || N % BN != 0) return MUW_ESHAPE;
+    if (int64_t(BK) * BN > 4096 || N > (int64_t(1) << 31) || K > (int64_t(1) << 31)) return MUW_EUNSUPPORTED;
+    if (!W_dev || !ws_dev) return MUW_EINVAL;
+    if (!aligned16(ws_dev)) return MUW_EINVAL;
+    const int64_t NB = (N / BN) * (K / BK);
+    int64_t n_u, n_p;
+    muw_status rc = muw_counts(NB, r_unify, r_prune, &n_u, &n_p);
+    if (rc != MUW_OK) return rc;
+    if (ws_bytes < unify_workspace_bytes(NB)) return MUW_ENOSPC;
+    bool nonfinite = false;
+    rc = launch_unify(N, K, BK, BN, W_dev, int(dtype), n_u, n_p, tags_dev, mags_dev, What_dev, ws_dev,
+                      static_cast<hipStream_t>(hip_stream), &nonfinite);
+    if (rc != MUW_OK) return rc;
+    return nonfinite ? MUW_ENONFINITE : MUW_OK;
+}
+
 muw_status muw_export(const muw_desc *desc, const void *blob_dev, uint8_t *tags_dev, uint16_t *signs_dev,
                       void *mags_dev, void *hip_stream)
 {

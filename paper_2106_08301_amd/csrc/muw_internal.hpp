@@ -43,6 +43,11 @@ muw_status select_k_smallest(uint64_t *keys, int64_t NB, int64_t k, void *sel_ws
                              uint64_t *other_keys, int poison, hipStream_t st);
 void launch_exclusive_scan(uint32_t *v, int64_t n, hipStream_t st);
 
+// muw_unify.hip: Unify() for a free 2-D block shape, written out dense
+size_t unify_workspace_bytes(int64_t NB);
+muw_status launch_unify(int64_t N, int64_t K, int BK, int BN, const void *W, int dtype, int64_t n_u, int64_t n_p,
+                        uint8_t *tags_out, void *mags_out, void *What, void *ws, hipStream_t st, bool *nonfinite);
+
 struct GemmArgs {
     const void *blob;        // single problem
     const void *X;

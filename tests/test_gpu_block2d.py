@@ -169,3 +169,63 @@ def test_mlp_shapes_at_full_size(muw, oracle, which):
     Y100 = muw.muw_gemm(layer, Xd[:100])
     rows = [0, 31, 99]
     check_close(to_f64(Y100[rows]), oracle.gemm(X.f64()[rows], What))
+
+
+# ---- Unify() for a free 2-D block shape, written out dense ---------------------------------------------------
+
+UNIFY_CASES = [
+    # N, K, BK, BN, dtype, r_u, r_p
+    (64, 96, 2, 2, "f32", 0.5, 0.25),          # the paper's [2,2]
+    (64, 96, 2, 2, "bf16", 0.6, 0.3),
+    (30, 48, 4, 2, "bf16", 0.4, 0.4),
+    (36, 40, 2, 3, "f32", 0.3, 0.5),
+    (16, 256, 8, 1, "bf16", 0.5, 0.4),         # one row high: Table 1's [8,1]
+    (128, 128, 16, 32, "bf16", 0.4, 0.5),      # the matrix-core operand shape
+    (8, 8, 8, 8, "f32", 1.0, 0.0),             # a single block
+    (12, 20, 1, 1, "f32", 0.5, 0.5),           # blocks of one weight: unified = kept, pruned = zeroed
+    (48, 64, 4, 4, "bf16", 0.0, 1.0),
+]
+
+
+@pytest.mark.parametrize("N,K,BK,BN,dtype,r_u,r_p", UNIFY_CASES)
+def test_unify_free_block_shape_is_bit_exact(muw, oracle, N, K, BK, BN, dtype, r_u, r_p):
+    W = synth.normal_tensor(1000 + N + K + BK, (N, K), 0.05, dtype, stream=1)
+    n_u, n_p = oracle.counts((N // BN) * (K // BK), r_u, r_p)
+    tags_o, mags_o, What_o = oracle.encode_2d(W.f64(), BK, BN, n_u, n_p,
+                                              oracle.STORE_F32 if dtype == "f32" else oracle.STORE_BF16)
+    tags, mags, What = muw.muw_unify(to_device(W), BK, BN, r_u, r_p)
+    assert np.array_equal(tags.cpu().numpy(), tags_o)
+    assert np.array_equal(to_f64(mags), mags_o)
+    assert np.array_equal(to_f64(What), What_o)
+
+
+def test_unify_agrees_with_the_packed_encoders(muw):
+    """The same projection through the packed formats: [16, 32] blocks and [8, 1] blocks."""
+    W = to_device(synth.normal_tensor(1100, (96, 256), 0.02, "bf16", stream=1))
+    tags, mags, What = muw.muw_unify(W, 16, 32, 0.4, 0.5)
+    layer = muw.muw_encode(W, 16, 0.4, 0.5, BN=32)
+    t2, _, m2 = muw.muw_export(layer)
+    assert torch.equal(tags, t2) and torch.equal(mags, m2) and torch.equal(What, muw.muw_decode(layer))
+    tags, mags, What = muw.muw_unify(W, 8, 1, 0.5, 0.3)
+    layer = muw.muw_encode(W, 8, 0.5, 0.3)
+    t2, _, m2 = muw.muw_export(layer)
+    assert torch.equal(tags, t2) and torch.equal(mags, m2) and torch.equal(What, muw.muw_decode(layer))
+
+
+def test_unify_rejected_arguments(muw):
+    lib = muw.lib
+    W = torch.zeros((6, 8), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    call = lambda N, K, BK, BN, ws_bytes=1 << 16, r=0.5: lib.muw_unify(N, K, BK, BN, W.data_ptr(), muw.MUW_F32, r, 0.2, None,
+                                                                        None, None, ws.data_ptr(), ws_bytes, None)
+    assert call(6, 8, 4, 4) == muw.MUW_ESHAPE             # 6 % 4 != 0
+    assert call(6, 8, 3, 2) == muw.MUW_ESHAPE             # 8 % 3 != 0
+    assert call(6, 8, 0, 2) == muw.MUW_EINVAL
+    assert call(6, 8, 2, 2, r=1.5) == muw.MUW_EINVAL
+    assert call(6, 8, 2, 2, ws_bytes=16) == muw.MUW_ENOSPC
+    assert call(6, 8, 2, 2) == muw.MUW_OK
+    assert lib.muw_unify_workspace_bytes(6, 8, 4, 4) == 0
+    Wn = W.clone()
+    Wn[1, 1] = float("inf")
+    assert lib.muw_unify(6, 8, 2, 2, Wn.data_ptr(), muw.MUW_F32, 0.5, 0.2, None, None, None, ws.data_ptr(), 1 << 16,
+                         None) == muw.MUW_ENONFINITE
