@@ -48,7 +48,8 @@ def parse():
     ap.add_argument("--groups", type=int, default=128, help="distinct encoded matrices per launch (cfg4)")
     ap.add_argument("--distinct", type=int, default=4, help="matrices generated from distinct seeds (cfg4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--report", action="store_true", help="also time the other configs (stderr + gpurun_out/report.json)")
+    ap.add_argument("--report", action="store_true", help="also time the other configs (table on stderr, rows in the file named by --report-file)")
+    ap.add_argument("--report-file", default=os.path.join(ROOT, "gpurun_out", "report.json"))
     return ap.parse_args()
 
 
@@ -341,8 +342,8 @@ def main():
     if args.report:
         rows = report_all(args, torch, muw, synth, to_device)
         line["all_configs"] = [{k: v for k, v in r.items() if k != "layers"} for r in rows]
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "report.json"), "w") as f:
+        os.makedirs(os.path.dirname(os.path.abspath(args.report_file)), exist_ok=True)
+        with open(args.report_file, "w") as f:
             json.dump(rows, f, indent=1)
     print(json.dumps(line))
 
