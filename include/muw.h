@@ -32,7 +32,7 @@
  * Block index j = s * (K / 16) + kc; the sums of the scores run over the block's rows in order and inside a row
  * over k in order.  Restrictions: bf16, MUW_LAYOUT_NK, N % 32 == 0, K % 16 == 0.  Supported entry points:
  * muw_encode_sizes, muw_encode, muw_export (signs_dev must be NULL: the signs are those of muw_decode's
- * output), muw_decode, muw_compressed_bytes, muw_gemm (no workspace; X 16-byte aligned, ldx % 8 == 0); the
+ * output), muw_decode, muw_compressed_bytes, muw_gemm_workspace_bytes, muw_gemm (X 16-byte aligned, ldx % 8 == 0); the
  * others return MUW_EUNSUPPORTED.
  */
 #ifndef MUW_H

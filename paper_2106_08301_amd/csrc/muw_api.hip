@@ -268,7 +268,11 @@ size_t muw_compressed_bytes(const muw_desc *desc)
 
 size_t muw_gemm_workspace_bytes(const muw_desc *desc, int64_t M)
 {
-    if (check_desc(desc) != MUW_OK || M < 0 || is_block2d(*desc)) return 0;
+    if (check_desc(desc) != MUW_OK || M < 0) return 0;
+    if (is_block2d(*desc)) {
+        Layout2 L2;
+        return M > 0 && layout2_of(desc, &L2) == MUW_OK ? block2d_gemm_workspace(L2, M) : 0;
+    }
     return gemm_workspace_bytes(*desc, layout_of(desc), M);
 }
 
@@ -289,7 +293,7 @@ muw_status muw_gemm(const muw_desc *desc, const void *blob_dev, const void *X_de
         Layout2 L2;
         rc = layout2_of(desc, &L2);
         if (rc != MUW_OK) return rc;
-        return launch_block2d_gemm(L2, blob_dev, X_dev, M, ldx, Y_dev, int(ydtype), ldy,
+        return launch_block2d_gemm(L2, blob_dev, X_dev, M, ldx, Y_dev, int(ydtype), ldy, ws_dev, ws_bytes,
                                    static_cast<hipStream_t>(hip_stream));
     }
     const Layout L = layout_of(desc);

@@ -75,7 +75,8 @@ muw_status launch_block2d_export(const Layout2 &L, const void *blob, uint8_t *ta
 muw_status launch_block2d_decode(const Layout2 &L, const void *blob, void *What, hipStream_t st);
 
 // muw_block2d_gemm.hip
+size_t block2d_gemm_workspace(const Layout2 &L, int64_t M);
 muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X, int64_t M, int64_t ldx, void *Y,
-                               int ydtype, int64_t ldy, hipStream_t st);
+                               int ydtype, int64_t ldy, void *ws, size_t ws_bytes, hipStream_t st);
 
 }  // namespace muw

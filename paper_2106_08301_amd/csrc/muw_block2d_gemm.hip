@@ -44,6 +44,8 @@ struct B2Args {
     uint64_t present_off, densemap_off, dir_off, mags_off, signs_off, dense_off;
     uint32_t n_ntiles, chunk, total;
     int32_t ydtype, vec_store;
+    uint32_t splits, slabs_per_split;  // K split over blockIdx.y: fp32 partial products in `part`, summed afterwards
+    float *part;
 };
 
 // (x & mask) | y in one instruction
@@ -82,7 +84,9 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     const uint32_t strip = ntile * kWaves + wave;
     const bool live = strip < a.NS;
     const uint32_t m0 = mtile * MT;
-    const uint32_t nslabs = (uint32_t(a.K) + kSlabK - 1) / kSlabK;
+    const uint32_t nslabs_all = (uint32_t(a.K) + kSlabK - 1) / kSlabK;
+    const uint32_t slab_lo = blockIdx.y * a.slabs_per_split;  // this workgroup's part of K (never empty)
+    const uint32_t nslabs = slab_lo + a.slabs_per_split < nslabs_all ? slab_lo + a.slabs_per_split : nslabs_all;
 
     // ---- activation slabs: DMA instruction i of this wave fills rows (8 i + wave) * 4 .. + 3 of the tile
     const uint32_t sub = uint32_t(lane) >> 4, pos = uint32_t(lane) & 15u;       // row inside the 4, chunk position
@@ -128,6 +132,14 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         ru = dir[0];
         rd = dir[1];
         ru_stop = dir[2];
+        // a later part of K starts at the ranks of its first block: count the blocks before it
+        const uint32_t kc_lo = slab_lo * (kSlabK / kB2K);
+        for (uint32_t g = 0; g * 64u < kc_lo; ++g) {
+            const uint64_t below = kc_lo - g * 64u >= 64u ? ~uint64_t(0) : (uint64_t(1) << (kc_lo - g * 64u)) - 1u;
+            const uint64_t p = present[g] & below, d = densemap[g] & below;
+            ru += uint32_t(__builtin_popcountll(p & ~d));
+            rd += uint32_t(__builtin_popcountll(d));
+        }
     }
     uint32_t q_next = ru >> 3, q_slot = q_next % 3u;  // next group to request, its ring slot
     uint32_t rslot = ru % 24u;                        // ring position of rank ru
@@ -152,10 +164,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
     uint64_t pw = 0, dw = 0;
-    issue_slab(0);
+    issue_slab(slab_lo);
     request_groups();
 #pragma unroll 1
-    for (uint32_t step = 0; step < nslabs; ++step) {
+    for (uint32_t step = slab_lo; step < nslabs; ++step) {
         // this wave's requests (slab `step`, payload groups) have landed, everybody's have, and everybody is done
         // with the slab before this one (its LDS reads were waited for before its MFMAs)
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         request_groups();
 
         // the 8 blocks of this slab: bits 8 (step % 8) .. + 7 of the strip's bitmap words
-        if ((step & 7u) == 0 && live) {
+        if (((step & 7u) == 0 || step == slab_lo) && live) {
             pw = present[step >> 3];
             dw = densemap[step >> 3];
         }
@@ -236,7 +248,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         for (int b = 0; b < 4; ++b) {
             const int64_t idx = int64_t(m) * a.ldy + n_lane + 8 * b;
             const float v0 = acc[i][4 * b], v1 = acc[i][4 * b + 1], v2 = acc[i][4 * b + 2], v3 = acc[i][4 * b + 3];
-            if (a.ydtype == MUW_F32) {
+            if (a.splits > 1) {
+                float *y = a.part + (uint64_t(blockIdx.y) * uint32_t(a.M) + m) * (uint64_t(a.NS) * kB2N) + n_lane + 8 * b;
+                *reinterpret_cast<float4 *>(y) = make_float4(v0, v1, v2, v3);
+            } else if (a.ydtype == MUW_F32) {
                 float *y = static_cast<float *>(a.Y) + idx;
                 if (a.vec_store) {
                     *reinterpret_cast<float4 *>(y) = make_float4(v0, v1, v2, v3);
@@ -263,20 +278,78 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     }
 }
 
+// Sum the K-split partial products in split order (deterministic) and write the output.
+__global__ __launch_bounds__(256) void k_block2d_reduce(const float *__restrict__ part, int splits, int64_t M, int64_t N,
+                                                        void *Y, int64_t ldy, int ydtype)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= M * N) return;
+    float t = 0.f;
+    for (int z = 0; z < splits; ++z) t += part[int64_t(z) * M * N + i];
+    const int64_t idx = (i / N) * ldy + i % N;
+    if (ydtype == MUW_F32)
+        static_cast<float *>(Y)[idx] = t;
+    else
+        static_cast<uint16_t *>(Y)[idx] = f32_to_bf16_rne(t);
+}
+
+// Rows per workgroup (32 MSUB) and K split for M activation rows: 128 rows when that still gives every compute
+// unit a workgroup, else 64 or 32 (more, smaller workgroups; each re-reads the compressed weights, which is the
+// cheap operand here); if even those leave most of the chip idle, K is split as well, at least 4 slabs a part.
+struct Shape {
+    int msub;
+    uint32_t n_mtiles, splits, slabs_per_split;
+};
+Shape choose_shape(const Layout2 &L, int64_t M)
+{
+    const uint64_t n_ntiles = uint64_t((L.NS + kWaves - 1) / kWaves), full = 256;
+    Shape s;
+    if (M > 64 && uint64_t((M + 127) / 128) * n_ntiles >= full)
+        s.msub = 4;
+    else if (M > 32 && uint64_t((M + 63) / 64) * n_ntiles >= full)
+        s.msub = 2;
+    else
+        s.msub = M > 128 ? 4 : 1;
+    s.n_mtiles = uint32_t((M + 32 * s.msub - 1) / (32 * s.msub));
+    const uint64_t wgs = uint64_t(s.n_mtiles) * n_ntiles;
+    const uint32_t nslabs = uint32_t((L.K + kSlabK - 1) / kSlabK);
+    uint32_t splits = 1;
+    if (wgs < full) {
+        splits = uint32_t((2 * full + wgs - 1) / wgs);
+        if (splits > nslabs / 4) splits = nslabs / 4;
+        if (splits < 1) splits = 1;
+    }
+    s.slabs_per_split = (nslabs + splits - 1) / splits;
+    s.splits = (nslabs + s.slabs_per_split - 1) / s.slabs_per_split;  // no empty part
+    return s;
+}
+
 template <int MSUB>
-muw_status launch(const B2Args &a0, uint32_t n_mtiles, hipStream_t st)
+muw_status launch(const B2Args &a0, const Shape &sh, hipStream_t st)
 {
     B2Args a = a0;
-    a.total = n_mtiles * a.n_ntiles;
+    a.total = sh.n_mtiles * a.n_ntiles;
     a.chunk = (a.total + 7u) / 8u;
-    k_block2d_gemm_bf16<MSUB><<<dim3(a.chunk * 8u), dim3(kWaves * 64), 0, st>>>(a);
+    a.splits = sh.splits;
+    a.slabs_per_split = sh.slabs_per_split;
+    k_block2d_gemm_bf16<MSUB><<<dim3(a.chunk * 8u, sh.splits), dim3(kWaves * 64), 0, st>>>(a);
+    if (sh.splits > 1) {
+        const int64_t N = int64_t(a.NS) * kB2N, total = int64_t(a.M) * N;
+        k_block2d_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.part, int(sh.splits), a.M, N, a.Y, a.ldy, a.ydtype);
+    }
     return hip_status(hipGetLastError());
 }
 
 }  // namespace
 
+size_t block2d_gemm_workspace(const Layout2 &L, int64_t M)
+{
+    const Shape sh = choose_shape(L, M);
+    return sh.splits > 1 ? size_t(sh.splits) * size_t(M) * size_t(L.N) * 4u : 0;
+}
+
 muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X, int64_t M, int64_t ldx, void *Y,
-                               int ydtype, int64_t ldy, hipStream_t st)
+                               int ydtype, int64_t ldy, void *ws, size_t ws_bytes, hipStream_t st)
 {
     // the DMA moves 16-byte chunks of activation rows
     if ((reinterpret_cast<uintptr_t>(X) & 15u) || (ldx & 7)) return MUW_EUNSUPPORTED;
@@ -300,13 +373,14 @@ muw_status launch_block2d_gemm(const Layout2 &L, const void *blob, const void *X
     a.ydtype = ydtype;
     const uint32_t ybytes = ydtype == MUW_F32 ? 4u : 2u;
     a.vec_store = ((reinterpret_cast<uintptr_t>(Y) & (4u * ybytes - 1u)) == 0 && (ldy & 3) == 0) ? 1 : 0;
-    // Rows per workgroup: 128 when that still gives every compute unit a workgroup, else 64 or 32 (more,
-    // smaller workgroups; each re-reads the compressed weights, which is the cheap operand here).
-    const uint64_t full = 256;
-    if (M > 64 && uint64_t((M + 127) / 128) * a.n_ntiles >= full) return launch<4>(a, uint32_t((M + 127) / 128), st);
-    if (M > 32 && uint64_t((M + 63) / 64) * a.n_ntiles >= full) return launch<2>(a, uint32_t((M + 63) / 64), st);
-    if (M > 128) return launch<4>(a, uint32_t((M + 127) / 128), st);
-    return launch<1>(a, uint32_t((M + 31) / 32), st);
+    const Shape sh = choose_shape(L, M);
+    if (sh.splits > 1) {
+        if (!ws || ws_bytes < block2d_gemm_workspace(L, M) || (reinterpret_cast<uintptr_t>(ws) & 15u)) return MUW_ENOSPC;
+        a.part = static_cast<float *>(ws);
+    }
+    if (sh.msub == 4) return launch<4>(a, sh, st);
+    if (sh.msub == 2) return launch<2>(a, sh, st);
+    return launch<1>(a, sh, st);
 }
 
 }  // namespace muw
