@@ -229,3 +229,23 @@ def test_unify_rejected_arguments(muw):
     Wn[1, 1] = float("inf")
     assert lib.muw_unify(6, 8, 2, 2, Wn.data_ptr(), muw.MUW_F32, 0.5, 0.2, None, None, None, ws.data_ptr(), 1 << 16,
                          None) == muw.MUW_ENONFINITE
+
+
+def test_gemm_on_seeded_random_shapes(muw, oracle):
+    """Shapes, ratios and row counts drawn from a seeded generator: every tile size, K split, ragged tail and
+    bitmap-word boundary gets hit by some case."""
+    rng = np.random.default_rng(20240611)
+    for case in range(14):
+        N = 32 * int(rng.integers(1, 11))
+        K = 16 * int(rng.integers(1, 90))
+        M = int(rng.integers(1, 260))
+        r_p = float(rng.choice([0.0, 0.25, 0.5, 0.8]))
+        r_u = float(rng.choice([0.0, 0.3, 0.6, 1.0])) * (1.0 - r_p)
+        W = synth.normal_tensor(2000 + case, (N, K), 0.02, "bf16", stream=1)
+        X = synth.normal_tensor(3000 + case, (M, K), 1.0, "bf16", stream=2)
+        layer, What = encode_both(muw, oracle, W, r_u, r_p)
+        Y = muw.muw_gemm(layer, to_device(X))
+        try:
+            check_close(to_f64(Y), oracle.gemm(X.f64(), What))
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: N={N} K={K} M={M} r_u={r_u} r_p={r_p}: {e}")
