@@ -48,7 +48,10 @@ struct TileGemmArgs {
 // Index (in 16-byte units) of chunk `chunk` of LDS row `row`.  Rows are 128 bytes (32 banks), so rows of
 // equal parity start at the same bank; XOR-ing the chunk with bits 1..3 of the row number makes the 16
 // rows that one quarter-wave reads at a fixed chunk hit 16 distinct 16-byte bank groups.
-__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }
+// XOR key of a 128-byte row: 8 consecutive rows get 8 different keys (no conflict among the 8 lanes that share a
+// 128-byte pass), and rows r, r + 8 differ in bit 0 of the key (none among 16 lanes over 64 banks either).
+__device__ inline int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ swz_key(row)); }
 
 // NCHW -> NHWC copy of a bf16 tensor (64 channels x 64 pixels per workgroup through LDS), so that the
 // implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.  With

@@ -289,7 +289,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int row = 8 * (wave * NA + i) + (lane >> 3);
-        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        const int chunk = (lane & 7) ^ swz_key(row);
         int64_t m = m0 + row;
         if (m >= a.M) m = a.M - 1;  // rows past the end compute values that are never stored
         avoff[i] = uint32_t((m * a.ldx + chunk * 8) * 2);
@@ -301,13 +301,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
                                              (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
     };
-    // operand reads: row = 16 x block + r, chunk 2 g + h sits at slot (2 g + h) ^ ((r >> 1) & 7)
+    // operand reads: row = 16 x block + r, chunk 2 g + h sits at slot (2 g + h) ^ swz_key(r)
     const uint32_t a_lds0 = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint8_t *)A_lds[0]));
     const uint32_t b_lds0 = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint4 *)B_lds[0]));
     uint32_t aaddr[2], baddr[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const uint32_t slot = uint32_t(((2 * g + h) ^ ((r >> 1) & 7)) * 16);
+        const uint32_t slot = uint32_t(((2 * g + h) ^ swz_key(r)) * 16);
         aaddr[h] = a_lds0 + uint32_t((wm * 64 + r) * 128) + slot;
         baddr[h] = b_lds0 + uint32_t((wn * 64 + r) * 128) + slot;
     }
