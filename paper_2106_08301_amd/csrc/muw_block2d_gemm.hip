@@ -2,10 +2,10 @@
 //
 // A workgroup of 8 wavefronts owns 32*MSUB activation rows and 256 output columns; wavefront w owns the
 // 32-row strip w of those columns for ALL of K and keeps its MSUB 32x32 accumulators in registers.
-//   - The activation tile goes HBM/L2 -> LDS in slabs of 128 k with global_load_lds (no registers), two
-//     slabs in flight (one being read, one landing).  A row of a slab is 256 contiguous bytes on both
-//     sides; its 16-byte chunks are stored XOR-swizzled with the row number so that the 64 lanes of a
-//     fragment read (32 rows x 2 chunks) hit distinct banks.
+//   - The activation tile goes HBM/L2 -> LDS in slabs of 128 k (256 k for 32-row workgroups) with
+//     global_load_lds (no registers), two slabs in flight (one being read, one landing).  A row of a slab is
+//     256 (512) contiguous bytes on both sides; its 16-byte chunks are stored XOR-swizzled with the row number
+//     so that the 64 lanes of a fragment read (32 rows x 2 chunks) hit distinct banks.
 //   - A wavefront walks the present-bitmap of its strip: a PRUNED block costs nothing at all -- no bytes,
 //     no decode, no MFMA (Sec. 3.2: pruned blocks are skipped).  The payload of UNIFIED blocks (a magnitude
 //     and one sign byte per lane) also comes through LDS by global_load_lds, a slab ahead of its use; the
@@ -32,7 +32,10 @@ typedef __attribute__((address_space(1))) void global_void;
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int kWaves = 8;
-constexpr int kSlabK = 128;
+// Block columns (of 16 k) per activation slab: 8 (128 k) for 64- and 128-row workgroups.  32-row workgroups, which
+// are bound by the round trip of each slab and not by the matrix pipe, take 16 (256 k): half the barriers per K,
+// and still two workgroups a compute unit (32 columns would leave room for one, and measured slower).
+constexpr int slab_kc(int msub) { return msub == 1 ? 16 : 8; }
 
 struct B2Args {
     const uint8_t *blob;
@@ -68,8 +71,15 @@ template <int MSUB>
 __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_block2d_gemm_bf16(B2Args a)
 {
     constexpr int MT = 32 * MSUB;
-    constexpr uint32_t kSlabBytes = uint32_t(MT) * kSlabK * 2u;
-    constexpr uint32_t kRingBytes = 3u * 512u + 64u;  // per wave: three groups of sign bytes and of magnitudes
+    constexpr int KCS = slab_kc(MSUB);                  // block columns per slab
+    constexpr uint32_t kSlabK = 16u * KCS;              // k per slab
+    constexpr uint32_t kRowBytes = 2u * kSlabK;         // one activation row of a slab
+    constexpr uint32_t kCpr = kRowBytes / 16u;          // its 16-byte chunks: 16 or 64
+    constexpr uint32_t kRowsPerDma = 64u / kCpr;        // rows one DMA instruction (1 KiB) fills
+    constexpr int kDma = MT * kRowBytes / 1024 / kWaves;  // DMA instructions per wave and slab
+    constexpr uint32_t kSlabBytes = uint32_t(MT) * kRowBytes;
+    constexpr uint32_t NG = KCS / 4 + 1;                // payload groups in the ring: the next 2 KCS ranks and a partial one
+    constexpr uint32_t kRingBytes = NG * 512u + ((NG * 16u + 63u) & ~63u);  // per wave: sign bytes, then magnitudes
     __shared__ __attribute__((aligned(1024))) uint8_t xs[2 * kSlabBytes + kWaves * kRingBytes];
 
     // Consecutive workgroup ids go to consecutive XCDs; give each XCD a contiguous run of the M-major tile
@@ -88,38 +98,40 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     const uint32_t slab_lo = blockIdx.y * a.slabs_per_split;  // this workgroup's part of K (never empty)
     const uint32_t nslabs = slab_lo + a.slabs_per_split < nslabs_all ? slab_lo + a.slabs_per_split : nslabs_all;
 
-    // ---- activation slabs: DMA instruction i of this wave fills rows (8 i + wave) * 4 .. + 3 of the tile
-    const uint32_t sub = uint32_t(lane) >> 4, pos = uint32_t(lane) & 15u;       // row inside the 4, chunk position
-    const uint32_t swz = pos ^ ((wave * 4u + sub) & 15u);                        // chunk of the row stored at `pos`
-    uint32_t xrow[MSUB];
+    // ---- activation slabs: DMA instruction i of this wave fills the KiB (8 i + wave) of the slab, i.e. rows
+    // (8 i + wave) * kRowsPerDma .. of the tile; a row's chunk c is stored at position c ^ (row % 16)
+    const uint32_t sub = uint32_t(lane) / kCpr, pos = uint32_t(lane) % kCpr;  // row inside the instruction's, chunk position
+    uint32_t xrow[kDma], xchunk[kDma];
 #pragma unroll
-    for (int i = 0; i < MSUB; ++i) {
-        xrow[i] = m0 + (uint32_t(i) * 8u + wave) * 4u + sub;
-        if (xrow[i] >= uint32_t(a.M)) xrow[i] = uint32_t(a.M) - 1u;
+    for (int i = 0; i < kDma; ++i) {
+        const uint32_t row = (uint32_t(i) * 8u + wave) * kRowsPerDma + sub;
+        xchunk[i] = pos ^ (row & 15u);
+        xrow[i] = m0 + row < uint32_t(a.M) ? m0 + row : uint32_t(a.M) - 1u;
     }
     auto issue_slab = [&](uint32_t j) __attribute__((always_inline)) {
-        uint32_t k = j * kSlabK + swz * 8u;
-        if (k >= uint32_t(a.K)) k = j * kSlabK;  // past the last column: any valid address, no block reads it
         uint8_t *dst = xs + (j & 1u) * kSlabBytes + wave * 1024u;
 #pragma unroll
-        for (int i = 0; i < MSUB; ++i)
+        for (int i = 0; i < kDma; ++i) {
+            uint32_t k = j * kSlabK + xchunk[i] * 8u;
+            if (k >= uint32_t(a.K)) k = j * kSlabK;  // past the last column: any valid address, no block reads it
             __builtin_amdgcn_global_load_lds((global_void *)(a.X + (uint64_t(xrow[i]) * uint64_t(a.ldx) + k)),
                                              (lds_void *)(dst + i * 8192), 16, 0, 0);
+        }
     };
 
-    // ---- fragment reads: lane (m = lane % 32, h = lane / 32) wants chunk 2 kc + h of row 32 mt + m
+    // ---- fragment reads: lane (m = lane % 32, h = lane / 32) wants chunk 2 b + h of row 32 mt + m
     const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t *)xs));
-    const uint32_t frag_base = lds_base + (uint32_t(lane) & 31u) * 256u;
+    const uint32_t frag_base = lds_base + (uint32_t(lane) & 31u) * kRowBytes;
     const uint32_t frag_swz = (uint32_t(lane) >> 5) ^ (uint32_t(lane) & 15u);
 
     // ---- the strip's payload.  Magnitudes and sign bytes of UNIFIED blocks are fetched in groups of 8
-    // consecutive blocks (group Q = payload ranks 8 Q .. 8 Q + 7: 16 + 512 bytes) into a per-wave ring of three
-    // groups.  Right after a slab barrier the wave requests the groups that hold the next 24 ranks; a slab uses
-    // at most 8, and the wait before the next barrier covers the requests: a rank is in the ring at least one
+    // consecutive blocks (group Q = payload ranks 8 Q .. 8 Q + 7: 16 + 512 bytes) into a per-wave ring of NG
+    // groups.  Right after a slab barrier the wave requests the groups that hold the next 2 KCS ranks; a slab uses
+    // at most KCS, and the wait before the next barrier covers the requests: a rank is in the ring at least one
     // slab before it can be needed, and no wait is ever spent on it alone.
     c_u64 *present = (c_u64 *)(a.blob + a.present_off) + uint64_t(strip) * a.W64;
     c_u64 *densemap = (c_u64 *)(a.blob + a.densemap_off) + uint64_t(strip) * a.W64;
-    const uint32_t ring_lds = lds_base + 2u * kSlabBytes + wave * kRingBytes;  // [3][512] sign bytes, [3][16] magnitudes
+    const uint32_t ring_lds = lds_base + 2u * kSlabBytes + wave * kRingBytes;  // [NG][512] sign bytes, [NG][16] magnitudes
     uint8_t *ring_ptr = xs + 2u * kSlabBytes + wave * kRingBytes;
     const uint32_t sign_lane = ring_lds + uint32_t(lane);
     const uint64_t sign_src = reinterpret_cast<uint64_t>(a.blob) + a.signs_off + uint32_t(lane & 31) * 16u;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         rd = dir[1];
         ru_stop = dir[2];
         // a later part of K starts at the ranks of its first block: count the blocks before it
-        const uint32_t kc_lo = slab_lo * (kSlabK / kB2K);
+        const uint32_t kc_lo = slab_lo * KCS;
         for (uint32_t g = 0; g * 64u < kc_lo; ++g) {
             const uint64_t below = kc_lo - g * 64u >= 64u ? ~uint64_t(0) : (uint64_t(1) << (kc_lo - g * 64u)) - 1u;
             const uint64_t p = present[g] & below, d = densemap[g] & below;
@@ -141,19 +153,19 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
             rd += uint32_t(__builtin_popcountll(d));
         }
     }
-    uint32_t q_next = ru >> 3, q_slot = q_next % 3u;  // next group to request, its ring slot
-    uint32_t rslot = ru % 24u;                        // ring position of rank ru
+    uint32_t q_next = ru >> 3, q_slot = q_next % NG;  // next group to request, its ring slot
+    uint32_t rslot = ru % (8u * NG);                  // ring position of rank ru
     auto request_groups = [&]() __attribute__((always_inline)) {
-        // (group q_next replaces group q_next - 3, whose last rank 8 q_next - 17 is below ru)
-        while (q_next * 8u <= ru + 16u && q_next * 8u < ru_stop) {
+        // (group q_next replaces group q_next - NG, whose last rank 8 q_next - 2 KCS - 1 is below ru)
+        while (q_next * 8u < ru + 2u * KCS && q_next * 8u < ru_stop) {
             if (lane < 32)
                 __builtin_amdgcn_global_load_lds((global_void *)(sign_src + uint64_t(q_next) * 512u),
                                                  (lds_void *)(ring_ptr + q_slot * 512u), 16, 0, 0);
             if (lane == 0)
                 __builtin_amdgcn_global_load_lds((global_void *)(mag_src + uint64_t(q_next) * 16u),
-                                                 (lds_void *)(ring_ptr + 1536u + q_slot * 16u), 16, 0, 0);
+                                                 (lds_void *)(ring_ptr + NG * 512u + q_slot * 16u), 16, 0, 0);
             ++q_next;
-            q_slot = q_slot == 2u ? 0u : q_slot + 1u;
+            q_slot = q_slot == NG - 1u ? 0u : q_slot + 1u;
         }
     };
 
@@ -174,29 +186,31 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         if (step + 1u < nslabs) issue_slab(step + 1u);
         request_groups();
 
-        // the 8 blocks of this slab: bits 8 (step % 8) .. + 7 of the strip's bitmap words
-        if (((step & 7u) == 0 || step == slab_lo) && live) {
-            pw = present[step >> 3];
-            dw = densemap[step >> 3];
+        // the KCS blocks of this slab: bits KCS (step % kSpw) .. + KCS - 1 of the strip's bitmap words
+        constexpr uint32_t kSpw = 64u / KCS;  // slabs per 64-bit bitmap word
+        constexpr uint32_t kBits = KCS == 32 ? 0xffffffffu : (1u << (KCS % 32)) - 1u;
+        if (((step % kSpw) == 0 || step == slab_lo) && live) {
+            pw = present[step / kSpw];
+            dw = densemap[step / kSpw];
         }
-        uint32_t p8 = uint32_t(pw >> ((step & 7u) * 8u)) & 0xffu;
-        const uint32_t d8 = uint32_t(dw >> ((step & 7u) * 8u)) & 0xffu;
+        uint32_t pbits = uint32_t(pw >> ((step % kSpw) * KCS)) & kBits;
+        const uint32_t dbits = uint32_t(dw >> ((step % kSpw) * KCS)) & kBits;
         const uint32_t slab_addr = frag_base + (step & 1u) * kSlabBytes;
-        while (p8 != 0) {
-            const uint32_t b = uint32_t(__builtin_ctz(p8));
-            p8 &= p8 - 1;
+        while (pbits != 0) {
+            const uint32_t b = uint32_t(__builtin_ctz(pbits));
+            pbits &= pbits - 1;
             const uint32_t addr = slab_addr + (((b * 2u) ^ frag_swz) << 4);
             u32x4 xf[MSUB];
             auto read_fragments = [&]() __attribute__((always_inline)) {
                 if constexpr (MSUB >= 1) xf[0] = lds_read_b128_at<0>(addr);
-                if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<8192>(addr);
+                if constexpr (MSUB >= 2) xf[1] = lds_read_b128_at<32 * kRowBytes>(addr);
                 if constexpr (MSUB >= 4) {
-                    xf[2] = lds_read_b128_at<16384>(addr);
-                    xf[3] = lds_read_b128_at<24576>(addr);
+                    xf[2] = lds_read_b128_at<64 * kRowBytes>(addr);
+                    xf[3] = lds_read_b128_at<96 * kRowBytes>(addr);
                 }
             };
             u32x4 wf;
-            if ((d8 >> b) & 1u) {
+            if ((dbits >> b) & 1u) {
                 read_fragments();
                 // (a DENSE block is fetched when it is met; its wait also covers the slab in flight)
                 const uint8_t *src = dense_lane + uint64_t(rd) * 1024u;
@@ -207,14 +221,14 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
                 uint32_t sb, mg;
                 asm volatile("ds_read_u8 %0, %2\n\tds_read_u16 %1, %3"
                              : "=&v"(sb), "=&v"(mg)
-                             : "v"(sign_lane + rslot * 64u), "v"(ring_lds + 1536u + rslot * 2u)
+                             : "v"(sign_lane + rslot * 64u), "v"(ring_lds + NG * 512u + rslot * 2u)
                              : "memory");
                 read_fragments();
                 if constexpr (MSUB == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(sb), "+v"(mg));
                 if constexpr (MSUB == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(sb), "+v"(mg));
                 if constexpr (MSUB == 4) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(sb), "+v"(mg));
                 ++ru;
-                rslot = rslot == 23u ? 0u : rslot + 1u;
+                rslot = rslot == 8u * NG - 1u ? 0u : rslot + 1u;
                 const uint32_t qq = mg | (mg << 16);
                 const uint32_t t = sb | (sb << 12);
 #pragma unroll
@@ -295,7 +309,7 @@ __global__ __launch_bounds__(256) void k_block2d_reduce(const float *__restrict_
 
 // Rows per workgroup (32 MSUB) and K split for M activation rows: 128 rows when that still gives every compute
 // unit a workgroup, else 64 or 32 (more, smaller workgroups; each re-reads the compressed weights, which is the
-// cheap operand here); if even those leave most of the chip idle, K is split as well, at least 4 slabs a part.
+// cheap operand here); if even those leave most of the chip idle, K is split as well, at least 512 k a part.
 struct Shape {
     int msub;
     uint32_t n_mtiles, splits, slabs_per_split;
@@ -312,11 +326,13 @@ Shape choose_shape(const Layout2 &L, int64_t M)
         s.msub = M > 128 ? 4 : 1;
     s.n_mtiles = uint32_t((M + 32 * s.msub - 1) / (32 * s.msub));
     const uint64_t wgs = uint64_t(s.n_mtiles) * n_ntiles;
-    const uint32_t nslabs = uint32_t((L.K + kSlabK - 1) / kSlabK);
+    const uint32_t slab_k = 16u * uint32_t(slab_kc(s.msub));
+    const uint32_t nslabs = uint32_t((L.K + slab_k - 1) / slab_k);
     uint32_t splits = 1;
     if (wgs < full) {
+        const uint32_t min_slabs = 512u / slab_k;  // at least 512 k a part
         splits = uint32_t((2 * full + wgs - 1) / wgs);
-        if (splits > nslabs / 4) splits = nslabs / 4;
+        if (splits > nslabs / min_slabs) splits = nslabs / min_slabs;
         if (splits < 1) splits = 1;
     }
     s.slabs_per_split = (nslabs + splits - 1) / splits;

@@ -171,6 +171,17 @@ def test_mlp_shapes_at_full_size(muw, oracle, which):
     check_close(to_f64(Y100[rows]), oracle.gemm(X.f64()[rows], What))
 
 
+def test_gemm_long_unified_runs_in_short_workgroups(muw, oracle):
+    """Few activation rows, many strips, 90 % unified: 32-row workgroups whose K parts hold more unified blocks
+    per strip than the kernel keeps payload groups in flight, so the payload ring wraps inside a part."""
+    W = synth.normal_tensor(811, (6656, 4096), 0.02, "bf16", stream=1)
+    layer, What = encode_both(muw, oracle, W, 0.9, 0.05)
+    for M in (128, 97):
+        X = synth.normal_tensor(912 + M, (M, 4096), 1.0, "bf16", stream=2)
+        Y = muw.muw_gemm(layer, to_device(X))
+        check_close(to_f64(Y), oracle.gemm(X.f64(), What))
+
+
 # ---- Unify() for a free 2-D block shape, written out dense ---------------------------------------------------
 
 UNIFY_CASES = [
