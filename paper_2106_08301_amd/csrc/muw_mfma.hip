@@ -43,6 +43,8 @@ struct TileGemmArgs {
     float *Ypart;
     // 1x1 convolution run as a linear layer on gathered pixels: Y is NCHW [M / pix][N][pix] (0: Y[M][ldy])
     int64_t pix;
+    // pipelined convolution: byte offset from X of 128 zero bytes (what a filter tap in the padding reads)
+    int64_t zero_off;
 };
 
 // Index (in 16-byte units) of chunk `chunk` of LDS row `row`.  Rows are 128 bytes (32 banks), so rows of
@@ -57,10 +59,18 @@ __device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ swz_ke
 // implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.  With
 // step > 1 only every step-th pixel of every step-th row is taken (OH x OW of them): the input of a
 // strided 1x1 convolution, which then is a plain GEMM over the gathered pixels.
+// Both copies also clear the 256 bytes at `zeros` (the page that stands for the padding), if given.
+__device__ inline void clear_zero_page(uint16_t *zeros)
+{
+    if (zeros && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 16)
+        reinterpret_cast<uint4 *>(zeros)[threadIdx.x] = make_uint4(0, 0, 0, 0);
+}
+
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                      int C, int H, int W, int OH, int OW, int step)
+                                                      int C, int H, int W, int OH, int OW, int step, uint16_t *zeros)
 {
     __shared__ uint16_t t[64][66];
+    clear_zero_page(zeros);
     const int64_t b = blockIdx.z;
     const int P = OH * OW;
     const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
@@ -82,9 +92,10 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict
 // aligned rows on both sides): 16-byte global loads (8 pixels of a channel) and stores (8 channels of a
 // pixel); the transposition happens in LDS, written 2 bytes at a time and read back as dwords.
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc_x8(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                         int C, int P)
+                                                         int C, int P, uint16_t *zeros)
 {
     __shared__ uint16_t t[64][66];  // [pixel][channel]; 33-dword rows spread the 2-byte writes over the banks
+    clear_zero_page(zeros);
     const int64_t b = blockIdx.z;
     const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
     const int grp = threadIdx.x & 7, row = threadIdx.x >> 3;  // 8 groups of 8 along the fast axis, 32 rows per pass
@@ -299,12 +310,19 @@ int tile_cus()
 // bytes per split, written and read again by the reduction), so it is worth it only when the plain
 // launch leaves most of the chip idle: below half of the resident workgroups for the kernel without
 // prefetch (which also needs the extra workgroups to hide its load latency), below a quarter for the
-// pipelined one (measured on the ResNet-50 layer shapes).  A split covers whole tiles.
+// pipelined one, or below half where K is long enough (32 panels) for half of the K loop to outweigh the
+// round trip (measured on the ResNet-50 layer shapes).  A split covers whole tiles.
+// Rows of a workgroup of the pipelined kernel: 256 (8 waves, one workgroup per compute unit: the decode of a strip
+// serves 256 rows), or 128 (4 waves, two per compute unit) for short M and for short K, where the 256-row
+// workgroup, alone on its compute unit, is mostly in prologue and epilogue while two 128-row ones overlap each
+// other's.
+int64_t pipe_tile_rows(const Layout &L, int64_t M) { return M > 128 && L.KP > 4 ? 256 : 128; }
+
 int tile_splits(const Layout &L, int64_t M, int64_t tm = 128, bool pipelined = false)
 {
     const int64_t wgs = ((L.N + kTN - 1) / kTN) * ((M + tm - 1) / tm);
     const int64_t resident = int64_t(tile_cus()) * (tm >= 256 ? 1 : 2);
-    if (wgs > resident / (pipelined ? 4 : 2) || L.KT < 2) return 1;
+    if (wgs > resident / (pipelined && L.KP < 32 ? 4 : 2) || L.KT < 2) return 1;
     // (the pipelined kernel's workgroups fill the chip exactly: one more than fits costs a whole second round)
     int64_t s = pipelined ? resident / wgs : (resident + wgs - 1) / wgs;
     if (s > L.KT) s = L.KT;
@@ -356,7 +374,7 @@ bool tile_gemm_applicable(const muw_desc &d, const Layout &L, const GemmArgs &a)
 size_t tile_gemm_workspace_bytes(const Layout &L, int64_t M)
 {
     // (whichever kernel takes the problem: the larger of the two split counts)
-    const int s = std::max(tile_splits(L, M), tile_splits(L, M, M > 128 ? 256 : 128, true));
+    const int s = std::max(tile_splits(L, M), tile_splits(L, M, pipe_tile_rows(L, M), true));
     return s > 1 ? size_t(s) * size_t(M) * size_t(L.N) * 4u : 0;
 }
 
@@ -390,24 +408,27 @@ bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
 }
 
 // NCHW -> NHWC staging of the input (step > 1: only the pixels a strided 1x1 convolution reads)
-void launch_nchw_to_nhwc(const ConvArgs &c, int Cin, int OH, int OW, int step, void *dst, hipStream_t st)
+void launch_nchw_to_nhwc(const ConvArgs &c, int Cin, int OH, int OW, int step, void *dst, hipStream_t st,
+                         uint16_t *zeros = nullptr)
 {
     const int P = OH * OW;
     dim3 tg(unsigned((P + 63) / 64), unsigned((Cin + 63) / 64), unsigned(c.Nb));
     const uint16_t *src = static_cast<const uint16_t *>(c.X);
     if (step == 1 && P % 8 == 0 && Cin % 8 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0)
-        k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P);
+        k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P, zeros);
     else
-        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step);
+        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step, zeros);
 }
 
 // 1x1, no padding (any stride): every output pixel reads exactly one input pixel
 bool conv_is_pointwise(const muw_desc &d, const ConvArgs &a) { return d.KH == 1 && d.KW == 1 && a.pad == 0; }
 
-size_t tile_conv_nhwc_bytes(const muw_desc &d, const ConvArgs &a)
+// The NHWC copy of the input, then (256-byte aligned) the zero page of the pipelined convolution.
+size_t tile_conv_zero_off(const muw_desc &d, const ConvArgs &a)
 {
-    return size_t(align16(uint64_t(a.Nb) * uint64_t(a.H) * uint64_t(a.W) * uint64_t(d.Cin) * 2u));
+    return size_t((uint64_t(a.Nb) * uint64_t(a.H) * uint64_t(a.W) * uint64_t(d.Cin) * 2u + 255u) & ~uint64_t(255));
 }
+size_t tile_conv_nhwc_bytes(const muw_desc &d, const ConvArgs &a) { return tile_conv_zero_off(d, a) + 256u; }
 
 size_t tile_conv_workspace_bytes(const muw_desc &d, const Layout &L, const ConvArgs &a)
 {
@@ -443,7 +464,8 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         default: break;
         }
     }
-    launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st);
+    const size_t zero_off = tile_conv_zero_off(d, c);
+    launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st, reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(ws) + zero_off));
     TileGemmArgs a{};
     a.blob = static_cast<const uint8_t *>(c.blob);
     a.X = static_cast<const uint16_t *>(ws);
@@ -458,6 +480,15 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     a.KW = d.KW;
     a.stride = c.stride;
     a.pad = c.pad;
+    a.zero_off = int64_t(zero_off);
+    {
+        // whole 64-channel panels: the pipelined kernel gathers them pixel by pixel
+        TileGemmArgs p = a;
+        p.ldy = L.N;
+        p.pix = c.OH * c.OW;
+        if (d.B == 8 && pipe_applicable<8>(p, L, true)) return launch_pipe<8, true>(p, L, part, part_bytes, st);
+        if (d.B == 16 && pipe_applicable<16>(p, L, true)) return launch_pipe<16, true>(p, L, part, part_bytes, st);
+    }
     switch (d.B) {
     case 4: return launch_tile_b<4, true>(a, L, part, part_bytes, st);
     case 8: return launch_tile_b<8, true>(a, L, part, part_bytes, st);

@@ -253,14 +253,19 @@ struct PipeArgs {
     int32_t M, ydtype;
     int64_t ldx, ldy;
     int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
-    int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a 1x1 convolution's output)
+    int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a convolution's output)
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
+    // CONV instantiation: X is the input as NHWC [Nb][H][W][Cin], Cin a multiple of 64, M = Nb*OH*OW and
+    // k = (kh*KW + kw)*Cin + cin, so a 64-k panel is 128 contiguous bytes of one input pixel -- or of the
+    // 128 zero bytes at X + zero_off where the filter tap falls into the padding
+    int32_t Cin, H, W, OH, OW, KW, stride, pad;
+    uint32_t zero_off;
 };
 
 // Macro tile TM x 128 x 64, NW waves as NW/2 x 2, wave tile 64 x 64 (TM = 32 NW).  NS = 8 / NW of the
 // eight strips of the tile are a wave's decode duty: with 8 waves the decode of a strip is shared by 256
 // rows of activations.
-template <int B, int NW>
+template <int B, int NW, bool CONV>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
 {
     constexpr int TM = 32 * NW;
@@ -285,21 +290,62 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 
     // ---- activation DMA: instruction i of this wave fills LDS rows 8 (wave NA + i) .. + 7; lane l is
     //      16-byte slot (row, l % 8) and fetches the chunk that the swizzle stores there
+    //      (convolution: row m is output pixel (image, oh, ow); its panel kp is the 64 channels c of the input
+    //      pixel (oh stride - pad + kh, ow stride - pad + kw) with (kh, kw, c / 64) = the digits of kp)
     uint32_t avoff[NA];
+    int32_t aih[NA], aiw[NA];  // CONV: input row and column of the row's filter tap (0, 0)
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int row = 8 * (wave * NA + i) + (lane >> 3);
         const int chunk = (lane & 7) ^ swz_key(row);
         int64_t m = m0 + row;
         if (m >= a.M) m = a.M - 1;  // rows past the end compute values that are never stored
-        avoff[i] = uint32_t((m * a.ldx + chunk * 8) * 2);
+        if constexpr (CONV) {
+            const uint32_t pix = uint32_t(a.OH) * uint32_t(a.OW);
+            const uint32_t img = uint32_t(m) / pix, rem = uint32_t(m) - img * pix;
+            const uint32_t oh = rem / uint32_t(a.OW), ow = rem - oh * uint32_t(a.OW);
+            aih[i] = int32_t(oh) * a.stride - a.pad;
+            aiw[i] = int32_t(ow) * a.stride - a.pad;
+            // (modulo 2^32: a negative row or column wraps, and the sum with a tap that makes the pixel valid is exact)
+            avoff[i] = ((img * uint32_t(a.H) + uint32_t(aih[i])) * uint32_t(a.W) + uint32_t(aiw[i])) * uint32_t(a.Cin) * 2u +
+                       uint32_t(chunk) * 16u;
+        } else {
+            avoff[i] = uint32_t((m * a.ldx + chunk * 8) * 2);
+        }
+    }
+    // CONV: digits of the next panel to request (requests go panel by panel from kp_lo on)
+    int t_kh = 0, t_kw = 0, t_c = 0;
+    if constexpr (CONV) {
+        const uint32_t cpp = uint32_t(a.Cin) / uint32_t(kPanelK), tap = uint32_t(kp_lo) / cpp;
+        t_c = int(uint32_t(kp_lo) - tap * cpp);
+        t_kh = int(tap / uint32_t(a.KW));
+        t_kw = int(tap - uint32_t(t_kh) * uint32_t(a.KW));
     }
     auto issue_a = [&](int kp, int buf) {
-        const uint64_t xk = reinterpret_cast<uint64_t>(a.X) + uint64_t(kp) * (kPanelK * 2);
+        if constexpr (CONV) {
+            const uint32_t tap_off = (uint32_t(t_kh * a.W + t_kw) * uint32_t(a.Cin) + uint32_t(t_c) * uint32_t(kPanelK)) * 2u;
+            const uint32_t zero = a.zero_off + uint32_t(lane & 7) * 16u;
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
-                                             (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+            for (int i = 0; i < NA; ++i) {
+                const bool inside = uint32_t(aih[i] + t_kh) < uint32_t(a.H) && uint32_t(aiw[i] + t_kw) < uint32_t(a.W);
+                const uint32_t off = inside ? avoff[i] + tap_off : zero;
+                __builtin_amdgcn_global_load_lds((global_void_t *)(reinterpret_cast<uint64_t>(a.X) + off),
+                                                 (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+            }
+            if (++t_c == a.Cin / kPanelK) {
+                t_c = 0;
+                if (++t_kw == a.KW) {
+                    t_kw = 0;
+                    ++t_kh;
+                }
+            }
+        } else {
+            const uint64_t xk = reinterpret_cast<uint64_t>(a.X) + uint64_t(kp) * (kPanelK * 2);
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
+                                                 (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+        }
     };
     // operand reads: row = 16 x block + r, chunk 2 g + h sits at slot (2 g + h) ^ swz_key(r)
     const uint32_t a_lds0 = uint32_t(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) uint8_t *)A_lds[0]));
@@ -601,8 +647,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         for (int i = 0; i < 6; ++i) atomicAdd(&g_tile_prof[i], (unsigned long long)tprof[i]);
 #endif
 
-    // ---- epilogue: lane holds Y[m = 4 g + v][n = r] of each 16 x 16 block
-    const bool nchw = a.pix && !a.Ypart;
+    // ---- epilogue: lane holds Y[m = 4 g + v][n = r] of each 16 x 16 block.  A K part writes its fp32 partial
+    // sums in the layout of the output (row-major or NCHW), so that the reduction is a flat sum.
+    const bool nchw = a.pix != 0;
+    float *part = a.Ypart ? a.Ypart + int64_t(blockIdx.z) * a.M * L.N : nullptr;
+    void *ydst = part ? static_cast<void *>(part) : a.Y;
+    const int ydtype = part ? int(MUW_F32) : a.ydtype;
+    const int64_t ldy = part && !nchw ? L.N : a.ldy;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int64_t mq = m0 + wm * 64 + mb * 16 + 4 * g;  // the lane's 4 consecutive rows
@@ -620,8 +671,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 // for a fixed output channel the lane's 4 rows are 4 consecutive pixels (of one image if
                 // the pixel count is a multiple of 4)
                 const int64_t pix = a.pix;
-                if ((pix & 3) == 0 && mq + 3 < a.M && a.ydtype == MUW_F32) {
-                    *reinterpret_cast<f32x4 *>(static_cast<float *>(a.Y) + (int64_t(img) * L.N + n) * pix + px) = acc[mb][s];
+                if ((pix & 3) == 0 && mq + 3 < a.M && ydtype == MUW_F32) {
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(ydst) + (int64_t(img) * L.N + n) * pix + px) = acc[mb][s];
                     continue;
                 }
 #pragma unroll
@@ -634,10 +685,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                         pi = uint32_t(mq + v) - bi * uint32_t(pix);
                     }
                     const int64_t idx = (int64_t(bi) * L.N + n) * pix + pi;
-                    if (a.ydtype == MUW_F32)
-                        static_cast<float *>(a.Y)[idx] = acc[mb][s][v];
+                    if (ydtype == MUW_F32)
+                        static_cast<float *>(ydst)[idx] = acc[mb][s][v];
                     else
-                        static_cast<uint16_t *>(a.Y)[idx] = f32_to_bf16_rne(acc[mb][s][v]);
+                        static_cast<uint16_t *>(ydst)[idx] = f32_to_bf16_rne(acc[mb][s][v]);
                 }
                 continue;
             }
@@ -645,33 +696,70 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             for (int v = 0; v < 4; ++v) {
                 const int64_t m = mq + v;
                 if (m >= a.M) continue;
-                if (a.Ypart)
-                    a.Ypart[(int64_t(blockIdx.z) * a.M + m) * L.N + n] = acc[mb][s][v];
-                else if (a.ydtype == MUW_F32)
-                    static_cast<float *>(a.Y)[m * a.ldy + n] = acc[mb][s][v];
+                if (ydtype == MUW_F32)
+                    static_cast<float *>(ydst)[m * ldy + n] = acc[mb][s][v];
                 else
-                    static_cast<uint16_t *>(a.Y)[m * a.ldy + n] = f32_to_bf16_rne(acc[mb][s][v]);
+                    static_cast<uint16_t *>(ydst)[m * ldy + n] = f32_to_bf16_rne(acc[mb][s][v]);
             }
         }
     }
 }
 
-// The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels.
+// Sum of the K parts' partial sums, which are in the layout of a dense output Y (row-major with ldy = N, or
+// NCHW): element by element, in split order (deterministic).
+__global__ __launch_bounds__(256) void k_flat_reduce(const float *__restrict__ part, int splits, int64_t total, void *Y,
+                                                     int ydtype)
+{
+    const int64_t i = (int64_t(blockIdx.x) * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
+    if (i + 3 < total) {
+        f32x4 t = *reinterpret_cast<const f32x4 *>(part + i);
+        for (int z = 1; z < splits; ++z) {
+            const f32x4 u = *reinterpret_cast<const f32x4 *>(part + int64_t(z) * total + i);
+            t[0] += u[0];
+            t[1] += u[1];
+            t[2] += u[2];
+            t[3] += u[3];
+        }
+        if (ydtype == MUW_F32 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0) {
+            *reinterpret_cast<f32x4 *>(static_cast<float *>(Y) + i) = t;
+            return;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (ydtype == MUW_F32)
+                static_cast<float *>(Y)[i + v] = t[v];
+            else
+                static_cast<uint16_t *>(Y)[i + v] = f32_to_bf16_rne(t[v]);
+        }
+        return;
+    }
+    for (int64_t j = i; j < total; ++j) {
+        float t = 0.f;
+        for (int z = 0; z < splits; ++z) t += part[int64_t(z) * total + j];
+        if (ydtype == MUW_F32)
+            static_cast<float *>(Y)[j] = t;
+        else
+            static_cast<uint16_t *>(Y)[j] = f32_to_bf16_rne(t);
+    }
+}
+
+// The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels, and
+// convolutions over an NHWC input (t.zero_off: where its 128 zero bytes are) whose Cin is one.
 template <int B>
-bool pipe_applicable(const TileGemmArgs &a, const Layout &L)
+bool pipe_applicable(const TileGemmArgs &a, const Layout &L, bool conv = false)
 {
     if (B != 8 && B != 16) return false;
     if (L.K % kPanelK != 0 || a.M < 1 || a.M >= (int64_t(1) << 30)) return false;
+    if (conv) return a.Cin % kPanelK == 0 && uint64_t(a.zero_off) + 128u < (uint64_t(1) << 32);
     return uint64_t(a.M) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);  // 32-bit DMA offsets
 }
 
-template <int B>
+template <int B, bool CONV = false>
 muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if constexpr (B == 8 || B == 16) {
-        // 256-row tiles with 8 waves (one workgroup per compute unit: the decode of a strip serves 256
-        // rows), 128-row tiles with 4 waves (two workgroups per compute unit) for short M
-        const int tm = t.M > 128 ? 256 : 128;
+        const int tm = int(pipe_tile_rows(L, t.M));
         int splits = tile_splits(L, t.M, tm, true);
         if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
         const int64_t kt_per = (L.KT + splits - 1) / splits;
@@ -687,16 +775,30 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.kp_per = int32_t(kt_per * kTilePanels);
         a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
+        if constexpr (CONV) {
+            a.Cin = t.Cin;
+            a.H = t.H;
+            a.W = t.W;
+            a.OH = t.OH;
+            a.OW = t.OW;
+            a.KW = t.KW;
+            a.stride = t.stride;
+            a.pad = t.pad;
+            a.zero_off = uint32_t(t.zero_off);
+        }
         const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
         dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
         if (tm == 256)
-            k_pipe_gemm_bf16<B, 8><<<grid, 512, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 8, CONV><<<grid, 512, 0, st>>>(a, L);
         else
-            k_pipe_gemm_bf16<B, 4><<<grid, 256, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 4, CONV><<<grid, 256, 0, st>>>(a, L);
         if (splits > 1) {
             const int64_t total = t.M * L.N;
-            k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, t.M, L.N, t.Y, t.ldy,
-                                                                        t.ydtype, t.pix);
+            if (t.pix || t.ldy == L.N)
+                k_flat_reduce<<<unsigned((total + 1023) / 1024), 256, 0, st>>>(a.Ypart, splits, total, t.Y, t.ydtype);
+            else
+                k_tile_reduce<<<unsigned((total + 255) / 256), 256, 0, st>>>(a.Ypart, splits, t.M, L.N, t.Y, t.ldy,
+                                                                            t.ydtype, 0);
         }
         return hip_status(hipGetLastError());
     } else {

@@ -276,6 +276,14 @@ CONV_CASES = [
     (3, 192, 12, 12, 136, 1, 1, 0, 8, "bf16"),    # M = 432: the 256-row tile, two column tiles
     (2, 64, 10, 6, 24, 1, 2, 0, 16, "bf16"),      # 15 output pixels per image: unaligned NCHW stores
     (1, 64, 1, 1, 16, 1, 1, 0, 8, "bf16"),        # one pixel
+    # k x k on whole 64-channel panels: the pipelined kernel gathers each panel from the input pixel of its
+    # filter tap, or from a page of zeros where the tap falls into the padding
+    (2, 64, 9, 10, 40, 3, 1, 1, 8, "bf16"),       # M = 180: the 256-row tile
+    (3, 128, 12, 12, 136, 3, 2, 1, 8, "bf16"),    # stride 2, M = 108: the 128-row tile, two column tiles
+    (2, 64, 8, 8, 24, 3, 1, 0, 16, "bf16"),       # no padding
+    (1, 192, 11, 7, 72, 5, 1, 2, 8, "bf16"),      # 5 x 5, 75 panels split over K: parts start inside a filter row
+    (5, 64, 17, 13, 130, 3, 1, 1, 8, "bf16"),     # M = 1105: several row tiles, images straddle them
+    (1, 64, 2, 2, 16, 3, 1, 1, 8, "bf16"),        # smaller than the filter: most taps are padding
 ]
 
 
