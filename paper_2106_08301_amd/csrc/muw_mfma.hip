@@ -444,16 +444,23 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     if (conv_is_pointwise(d, c)) {
         // a 1x1 convolution without padding is a linear layer over the (sampled) pixels
         const int P = int(c.OH * c.OW);
-        launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
         TileGemmArgs a{};
         a.blob = static_cast<const uint8_t *>(c.blob);
-        a.X = static_cast<const uint16_t *>(ws);
         a.Y = c.Y;
         a.M = c.Nb * c.OH * c.OW;
         a.ldx = d.Cin;
         a.ldy = L.N;
         a.ydtype = c.ydtype;
         a.pix = P;
+        a.Cin = d.Cin;
+        if (c.stride == 1) {
+            // every pixel is read: the pipelined kernel takes the channel planes as they are
+            a.X = static_cast<const uint16_t *>(c.X);
+            if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes>(a, L, part, part_bytes, st);
+            if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes)) return launch_pipe<16, kXPlanes>(a, L, part, part_bytes, st);
+        }
+        launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
+        a.X = static_cast<const uint16_t *>(ws);
         switch (d.B) {
         case 8:
             if (pipe_applicable<8>(a, L)) return launch_pipe<8>(a, L, part, part_bytes, st);
@@ -486,8 +493,8 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         TileGemmArgs p = a;
         p.ldy = L.N;
         p.pix = c.OH * c.OW;
-        if (d.B == 8 && pipe_applicable<8>(p, L, true)) return launch_pipe<8, true>(p, L, part, part_bytes, st);
-        if (d.B == 16 && pipe_applicable<16>(p, L, true)) return launch_pipe<16, true>(p, L, part, part_bytes, st);
+        if (d.B == 8 && pipe_applicable<8>(p, L, kXConv)) return launch_pipe<8, kXConv>(p, L, part, part_bytes, st);
+        if (d.B == 16 && pipe_applicable<16>(p, L, kXConv)) return launch_pipe<16, kXConv>(p, L, part, part_bytes, st);
     }
     switch (d.B) {
     case 4: return launch_tile_b<4, true>(a, L, part, part_bytes, st);

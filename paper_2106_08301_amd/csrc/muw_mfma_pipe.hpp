@@ -255,17 +255,37 @@ struct PipeArgs {
     int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
     int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a convolution's output)
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
-    // CONV instantiation: X is the input as NHWC [Nb][H][W][Cin], Cin a multiple of 64, M = Nb*OH*OW and
+    // kXConv: X is the input as NHWC [Nb][H][W][Cin], Cin a multiple of 64, M = Nb*OH*OW and
     // k = (kh*KW + kw)*Cin + cin, so a 64-k panel is 128 contiguous bytes of one input pixel -- or of the
-    // 128 zero bytes at X + zero_off where the filter tap falls into the padding
+    // 128 zero bytes at X + zero_off where the filter tap falls into the padding.
+    // kXPlanes: X is NCHW [M / pix][Cin][pix] (the input of a 1x1 convolution as it is), pix a multiple of 8:
+    // 8 consecutive rows of one k are 16 contiguous bytes.
     int32_t Cin, H, W, OH, OW, KW, stride, pad;
     uint32_t zero_off;
 };
 
+// Where the kernel's activation rows come from.
+constexpr int kXRows = 0;    // X[M][ldx], k contiguous
+constexpr int kXConv = 1;    // gathered from an NHWC image, 64 channels of a pixel at a time
+constexpr int kXPlanes = 2;  // channel planes (NCHW): the tile is kept k-major in LDS and read through the transposing load
+
+// ds_read_b64_tr_b16: within 16 lanes, lane 4 q + j receives element j of the 8 bytes addressed by lanes q, 4 + q,
+// 8 + q, 12 + q (in that order).  With lane 4 e + q addressing pixels 4 q .. 4 q + 3 of channel k0 + e, lane r ends
+// up with channels k0 .. k0 + 3 of pixel r: half of a matrix-core operand.  (Inline assembly for the same reason as
+// the other reads of DMA-filled LDS.)
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <int OFF>
+__device__ inline u32x2_t lds_read_tr16_b64_at(uint32_t addr)
+{
+    u32x2_t v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
 // Macro tile TM x 128 x 64, NW waves as NW/2 x 2, wave tile 64 x 64 (TM = 32 NW).  NS = 8 / NW of the
 // eight strips of the tile are a wave's decode duty: with 8 waves the decode of a strip is shared by 256
 // rows of activations.
-template <int B, int NW, bool CONV>
+template <int B, int NW, int XM>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
 {
     constexpr int TM = 32 * NW;
@@ -293,14 +313,29 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     //      (convolution: row m is output pixel (image, oh, ow); its panel kp is the 64 channels c of the input
     //      pixel (oh stride - pad + kh, ow stride - pad + kw) with (kh, kw, c / 64) = the digits of kp)
     uint32_t avoff[NA];
-    int32_t aih[NA], aiw[NA];  // CONV: input row and column of the row's filter tap (0, 0)
+    //      (channel planes: the tile is [64 k][TM rows]; instruction i fills the KiB (wave NA + i) of it, lane l the
+    //      16-byte slot l of that: 8 rows of one k.  The 32-byte segments of a k-row are XOR-swizzled with
+    //      tr_key(k), which gives the 16 k-rows that one transposing read touches (16 g + e + a constant) distinct keys)
+    constexpr int RB = TM * 2;  // kXPlanes: bytes of a k-row
+    auto tr_key = [](int k) { return ((k & 3) | (((k >> 4) & 3) << 2)) & (TM / 16 - 1); };
+    int32_t aih[NA], aiw[NA];  // kXConv: input row and column of the row's filter tap (0, 0)
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
+        if constexpr (XM == kXPlanes) {
+            const int byte = (wave * NA + i) * 1024 + lane * 16;
+            const int k = byte / RB, pos = (byte % RB) / 16;
+            const int seg = (pos >> 1) ^ tr_key(k);
+            int64_t m = m0 + seg * 16 + (pos & 1) * 8;
+            if (m >= a.M) m = a.M - 8;  // (M is a multiple of 8) rows past the end compute values that are never stored
+            const uint32_t img = uint32_t(m) / uint32_t(a.pix), px = uint32_t(m) - img * uint32_t(a.pix);
+            avoff[i] = ((img * uint32_t(a.Cin) + uint32_t(k)) * uint32_t(a.pix) + px) * 2u;
+            continue;
+        }
         const int row = 8 * (wave * NA + i) + (lane >> 3);
         const int chunk = (lane & 7) ^ swz_key(row);
         int64_t m = m0 + row;
         if (m >= a.M) m = a.M - 1;  // rows past the end compute values that are never stored
-        if constexpr (CONV) {
+        if constexpr (XM == kXConv) {
             const uint32_t pix = uint32_t(a.OH) * uint32_t(a.OW);
             const uint32_t img = uint32_t(m) / pix, rem = uint32_t(m) - img * pix;
             const uint32_t oh = rem / uint32_t(a.OW), ow = rem - oh * uint32_t(a.OW);
@@ -313,16 +348,22 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             avoff[i] = uint32_t((m * a.ldx + chunk * 8) * 2);
         }
     }
-    // CONV: digits of the next panel to request (requests go panel by panel from kp_lo on)
+    // kXConv: digits of the next panel to request (requests go panel by panel from kp_lo on)
     int t_kh = 0, t_kw = 0, t_c = 0;
-    if constexpr (CONV) {
+    if constexpr (XM == kXConv) {
         const uint32_t cpp = uint32_t(a.Cin) / uint32_t(kPanelK), tap = uint32_t(kp_lo) / cpp;
         t_c = int(uint32_t(kp_lo) - tap * cpp);
         t_kh = int(tap / uint32_t(a.KW));
         t_kw = int(tap - uint32_t(t_kh) * uint32_t(a.KW));
     }
     auto issue_a = [&](int kp, int buf) {
-        if constexpr (CONV) {
+        if constexpr (XM == kXPlanes) {
+            const uint64_t xk = reinterpret_cast<uint64_t>(a.X) + uint64_t(kp) * uint64_t(a.pix) * (kPanelK * 2);
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
+                                                 (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+        } else if constexpr (XM == kXConv) {
             const uint32_t tap_off = (uint32_t(t_kh * a.W + t_kw) * uint32_t(a.Cin) + uint32_t(t_c) * uint32_t(kPanelK)) * 2u;
             const uint32_t zero = a.zero_off + uint32_t(lane & 7) * 16u;
 #pragma unroll
@@ -356,6 +397,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         const uint32_t slot = uint32_t(((2 * g + h) ^ swz_key(r)) * 16);
         aaddr[h] = a_lds0 + uint32_t((wm * 64 + r) * 128) + slot;
         baddr[h] = b_lds0 + uint32_t((wn * 64 + r) * 128) + slot;
+    }
+    // kXPlanes: lane 16 g + 4 e + q addresses pixels 4 q .. + 3 of the 16-row block in k-row 16 g + e (+ 8 h + 4 j
+    // as the instruction's offset: like the other operand, lane group g holds k = 16 g + 8 h .. + 7 of the panel in
+    // half h); block mb is segment 4 wm + mb of the row, swizzled with the row's key
+    uint32_t atr[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int k = 16 * g + (r >> 2);
+        atr[mb] = a_lds0 + uint32_t(k * RB + (((wm * 4 + mb) ^ tr_key(k)) * 32) + (r & 3) * 8);
     }
 
     // ---- decode duty: strips NS wave .. NS wave + NS - 1 of the tile's eight
@@ -479,6 +529,38 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         const uint32_t a0 = aaddr[0] + uint32_t(abuf) * ABYTES, a1 = aaddr[1] + uint32_t(abuf) * ABYTES;
         u32x4_t bf[4][2];
         u32x4_t af[2][2];
+        u32x2_t at[2][4];  // kXPlanes: [buffer][2 h + j] = k 16 g + 8 h + 4 j .. + 3 of the lane's row
+        // A fragments of 16-row block mb into buffer c (2 reads, or 4 transposing ones), and the wait for them
+        // while those of the next block (if any) are in flight
+        auto read_a = [&](int c, auto mbc) __attribute__((always_inline)) {
+            constexpr int mb = decltype(mbc)::value;
+            if constexpr (XM == kXPlanes) {
+                const uint32_t ab = atr[mb] + uint32_t(abuf) * ABYTES;
+                at[c][0] = lds_read_tr16_b64_at<0>(ab);
+                at[c][1] = lds_read_tr16_b64_at<4 * RB>(ab);
+                at[c][2] = lds_read_tr16_b64_at<8 * RB>(ab);
+                at[c][3] = lds_read_tr16_b64_at<12 * RB>(ab);
+            } else {
+                // (the offset is an immediate of the instruction)
+                af[c][0] = lds_read_b128_at<mb * 2048>(a0);
+                af[c][1] = lds_read_b128_at<mb * 2048>(a1);
+            }
+        };
+        auto wait_a = [&](int c, bool more_in_flight) __attribute__((always_inline)) {
+            if constexpr (XM == kXPlanes) {
+                if (more_in_flight)
+                    asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(at[c][0]), "+v"(at[c][1]), "+v"(at[c][2]), "+v"(at[c][3]));
+                else
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(at[c][0]), "+v"(at[c][1]), "+v"(at[c][2]), "+v"(at[c][3]));
+                af[c][0] = u32x4_t{at[c][0].x, at[c][0].y, at[c][1].x, at[c][1].y};
+                af[c][1] = u32x4_t{at[c][2].x, at[c][2].y, at[c][3].x, at[c][3].y};
+            } else {
+                if (more_in_flight)
+                    asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                else
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[c][0]), "+v"(af[c][1]));
+            }
+        };
 
         // ---- prefetches: activation tile, masks, payload, directory entries
         auto prefetch = [&]() __attribute__((always_inline)) {
@@ -526,11 +608,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
                 bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
             }
-            af[0][0] = lds_read_b128_at<0>(a0);
-            af[0][1] = lds_read_b128_at<0>(a1);
-            asm volatile("s_waitcnt lgkmcnt(2)"
-                         : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
-                           "+v"(bf[2][1]), "+v"(bf[3][1]));
+            read_a(0, std::integral_constant<int, 0>{});
+            if constexpr (XM == kXPlanes)
+                asm volatile("s_waitcnt lgkmcnt(4)"
+                             : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
+                               "+v"(bf[2][1]), "+v"(bf[3][1]));
+            else
+                asm volatile("s_waitcnt lgkmcnt(2)"
+                             : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
+                               "+v"(bf[2][1]), "+v"(bf[3][1]));
             TPROF_MARK(1);  // B fragment reads
         };
         // ---- decode of the next step's weights into the other buffer
@@ -554,23 +640,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             for (int mb = 0; mb < MB; ++mb) {
                 const int c = mb & 1;
                 if (mb + 1 < MB) {
-                    // (the offset is an immediate of the instruction: spell the cases out)
-                    auto rd = [&](auto mbc) {
-                        constexpr int OFF = decltype(mbc)::value * 2048;
-                        af[c ^ 1][0] = lds_read_b128_at<OFF>(a0);
-                        af[c ^ 1][1] = lds_read_b128_at<OFF>(a1);
-                    };
-                    if (mb == 0) rd(std::integral_constant<int, 1>{});
-                    if (mb == 1) rd(std::integral_constant<int, 2>{});
-                    if (mb == 2) rd(std::integral_constant<int, 3>{});
-                    if (mb == 3) rd(std::integral_constant<int, 4 % MB>{});
-                    if (mb == 4) rd(std::integral_constant<int, 5 % MB>{});
-                    if (mb == 5) rd(std::integral_constant<int, 6 % MB>{});
-                    if (mb == 6) rd(std::integral_constant<int, 7 % MB>{});
-                    asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[c][0]), "+v"(af[c][1]));
-                } else {
-                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[c][0]), "+v"(af[c][1]));
+                    // (the block number is a template argument: spell the cases out)
+                    if (mb == 0) read_a(c ^ 1, std::integral_constant<int, 1>{});
+                    if (mb == 1) read_a(c ^ 1, std::integral_constant<int, 2>{});
+                    if (mb == 2) read_a(c ^ 1, std::integral_constant<int, 3>{});
                 }
+                static_assert(MB == 4, "the cases above");
+                wait_a(c, mb + 1 < MB);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -744,18 +820,22 @@ __global__ __launch_bounds__(256) void k_flat_reduce(const float *__restrict__ p
     }
 }
 
-// The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels, and
-// convolutions over an NHWC input (t.zero_off: where its 128 zero bytes are) whose Cin is one.
+// The pipelined kernel takes linear layers with B = 8 or 16 whose K is a whole number of panels, convolutions
+// over an NHWC input (t.zero_off: where its 128 zero bytes are) whose Cin is one, and 1x1 convolutions straight
+// from a 16-byte aligned NCHW input whose images have a multiple of 8 pixels.
 template <int B>
-bool pipe_applicable(const TileGemmArgs &a, const Layout &L, bool conv = false)
+bool pipe_applicable(const TileGemmArgs &a, const Layout &L, int xm = kXRows)
 {
     if (B != 8 && B != 16) return false;
     if (L.K % kPanelK != 0 || a.M < 1 || a.M >= (int64_t(1) << 30)) return false;
-    if (conv) return a.Cin % kPanelK == 0 && uint64_t(a.zero_off) + 128u < (uint64_t(1) << 32);
+    if (xm == kXConv) return a.Cin % kPanelK == 0 && uint64_t(a.zero_off) + 128u < (uint64_t(1) << 32);
+    if (xm == kXPlanes)
+        return a.pix % 8 == 0 && a.Cin == L.K && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0 &&
+               uint64_t(a.M) * uint64_t(L.K) * 2u < (uint64_t(1) << 32);
     return uint64_t(a.M) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);  // 32-bit DMA offsets
 }
 
-template <int B, bool CONV = false>
+template <int B, int XM = kXRows>
 muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if constexpr (B == 8 || B == 16) {
@@ -775,7 +855,8 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.kp_per = int32_t(kt_per * kTilePanels);
         a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
-        if constexpr (CONV) {
+        if constexpr (XM == kXPlanes) a.Cin = t.Cin;
+        if constexpr (XM == kXConv) {
             a.Cin = t.Cin;
             a.H = t.H;
             a.W = t.W;
@@ -789,9 +870,9 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
         dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
         if (tm == 256)
-            k_pipe_gemm_bf16<B, 8, CONV><<<grid, 512, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 8, XM><<<grid, 512, 0, st>>>(a, L);
         else
-            k_pipe_gemm_bf16<B, 4, CONV><<<grid, 256, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 4, XM><<<grid, 256, 0, st>>>(a, L);
         if (splits > 1) {
             const int64_t total = t.M * L.N;
             if (t.pix || t.ldy == L.N)

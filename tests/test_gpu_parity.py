@@ -276,6 +276,13 @@ CONV_CASES = [
     (3, 192, 12, 12, 136, 1, 1, 0, 8, "bf16"),    # M = 432: the 256-row tile, two column tiles
     (2, 64, 10, 6, 24, 1, 2, 0, 16, "bf16"),      # 15 output pixels per image: unaligned NCHW stores
     (1, 64, 1, 1, 16, 1, 1, 0, 8, "bf16"),        # one pixel
+    # 1x1, stride 1, images of a multiple of 8 pixels: the pipelined kernel reads the channel planes as they are
+    # (k-major tile in LDS, transposing reads)
+    (2, 128, 8, 4, 72, 1, 1, 0, 16, "bf16"),      # M = 64: half of a 128-row tile is past the end
+    (5, 64, 8, 5, 40, 1, 1, 0, 8, "bf16"),        # 40 pixels per image: 16-row blocks straddle images
+    (2, 320, 16, 16, 200, 1, 1, 0, 8, "bf16"),    # 5 panels, two 256-row tiles, two column tiles
+    (1, 2048, 4, 4, 64, 1, 1, 0, 8, "bf16"),      # M = 16, K = 2048: split over K
+    (3, 64, 24, 24, 24, 1, 1, 0, 8, "bf16"),      # M = 1728: 128-row tiles (one panel), ragged last tile
     # k x k on whole 64-channel panels: the pipelined kernel gathers each panel from the input pixel of its
     # filter tap, or from a page of zeros where the tap falls into the padding
     (2, 64, 9, 10, 40, 3, 1, 1, 8, "bf16"),       # M = 180: the 256-row tile
