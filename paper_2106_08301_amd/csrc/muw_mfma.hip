@@ -458,6 +458,8 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
             a.X = static_cast<const uint16_t *>(c.X);
             if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes>(a, L, part, part_bytes, st);
             if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes)) return launch_pipe<16, kXPlanes>(a, L, part, part_bytes, st);
+            if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes2)) return launch_pipe<8, kXPlanes2>(a, L, part, part_bytes, st);
+            if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes2)) return launch_pipe<16, kXPlanes2>(a, L, part, part_bytes, st);
         }
         launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
         a.X = static_cast<const uint16_t *>(ws);

@@ -259,7 +259,7 @@ struct PipeArgs {
     // k = (kh*KW + kw)*Cin + cin, so a 64-k panel is 128 contiguous bytes of one input pixel -- or of the
     // 128 zero bytes at X + zero_off where the filter tap falls into the padding.
     // kXPlanes: X is NCHW [M / pix][Cin][pix] (the input of a 1x1 convolution as it is), pix a multiple of 8:
-    // 8 consecutive rows of one k are 16 contiguous bytes.
+    // 8 consecutive rows of one k are 16 contiguous bytes.  kXPlanes2: pix even, 2 rows are 4 contiguous bytes.
     int32_t Cin, H, W, OH, OW, KW, stride, pad;
     uint32_t zero_off;
 };
@@ -268,6 +268,7 @@ struct PipeArgs {
 constexpr int kXRows = 0;    // X[M][ldx], k contiguous
 constexpr int kXConv = 1;    // gathered from an NHWC image, 64 channels of a pixel at a time
 constexpr int kXPlanes = 2;  // channel planes (NCHW): the tile is kept k-major in LDS and read through the transposing load
+constexpr int kXPlanes2 = 3;  // the same for images of an even number of pixels: DMA of 2 rows (4 bytes) instead of 8
 
 // ds_read_b64_tr_b16: within 16 lanes, lane 4 q + j receives element j of the 8 bytes addressed by lanes q, 4 + q,
 // 8 + q, 12 + q (in that order).  With lane 4 e + q addressing pixels 4 q .. 4 q + 3 of channel k0 + e, lane r ends
@@ -291,7 +292,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     constexpr int TM = 32 * NW;
     constexpr int NS = 8 / NW;         // strips decoded by a wave
     constexpr int MB = 4;              // 16-row blocks per wave
-    constexpr int NA = 4;              // activation DMA instructions per wave and step (8 rows of 128 bytes each)
+    constexpr bool PLANES = XM == kXPlanes || XM == kXPlanes2;
+    constexpr int DW = XM == kXPlanes2 ? 4 : 16;  // bytes a lane moves per activation DMA instruction
+    constexpr int NA = 64 / DW;        // activation DMA instructions per wave and step (64 DW bytes each; 4: 8 rows of 128 bytes)
     constexpr int ABYTES = TM * 128;   // one activation buffer
     constexpr int BBYTES = kTN * 128;  // one weight buffer
     constexpr int NAB = NW == 8 ? 3 : 2;  // activation buffers (three fit only with one workgroup per compute unit)
@@ -321,12 +324,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     int32_t aih[NA], aiw[NA];  // kXConv: input row and column of the row's filter tap (0, 0)
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        if constexpr (XM == kXPlanes) {
-            const int byte = (wave * NA + i) * 1024 + lane * 16;
-            const int k = byte / RB, pos = (byte % RB) / 16;
-            const int seg = (pos >> 1) ^ tr_key(k);
-            int64_t m = m0 + seg * 16 + (pos & 1) * 8;
-            if (m >= a.M) m = a.M - 8;  // (M is a multiple of 8) rows past the end compute values that are never stored
+        if constexpr (PLANES) {
+            const int byte = (wave * NA + i) * (64 * DW) + lane * DW;
+            const int k = byte / RB, pos = (byte % RB) / 32, in_seg = byte % 32;
+            const int seg = pos ^ tr_key(k);
+            int64_t m = m0 + seg * 16 + in_seg / 2;
+            if (m >= a.M) m = a.M - DW / 2;  // (M is a multiple of DW / 2) rows past the end compute values that are never stored
             const uint32_t img = uint32_t(m) / uint32_t(a.pix), px = uint32_t(m) - img * uint32_t(a.pix);
             avoff[i] = ((img * uint32_t(a.Cin) + uint32_t(k)) * uint32_t(a.pix) + px) * 2u;
             continue;
@@ -357,12 +360,18 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         t_kw = int(tap - uint32_t(t_kh) * uint32_t(a.KW));
     }
     auto issue_a = [&](int kp, int buf) {
-        if constexpr (XM == kXPlanes) {
+        if constexpr (PLANES) {
             const uint64_t xk = reinterpret_cast<uint64_t>(a.X) + uint64_t(kp) * uint64_t(a.pix) * (kPanelK * 2);
 #pragma unroll
-            for (int i = 0; i < NA; ++i)
-                __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
-                                                 (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+            for (int i = 0; i < NA; ++i) {
+                // (the size is an immediate of the builtin)
+                if constexpr (XM == kXPlanes2)
+                    __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
+                                                     (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 256), 4, 0, 0);
+                else
+                    __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
+                                                     (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+            }
         } else if constexpr (XM == kXConv) {
             const uint32_t tap_off = (uint32_t(t_kh * a.W + t_kw) * uint32_t(a.Cin) + uint32_t(t_c) * uint32_t(kPanelK)) * 2u;
             const uint32_t zero = a.zero_off + uint32_t(lane & 7) * 16u;
@@ -534,7 +543,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         // while those of the next block (if any) are in flight
         auto read_a = [&](int c, auto mbc) __attribute__((always_inline)) {
             constexpr int mb = decltype(mbc)::value;
-            if constexpr (XM == kXPlanes) {
+            if constexpr (PLANES) {
                 const uint32_t ab = atr[mb] + uint32_t(abuf) * ABYTES;
                 at[c][0] = lds_read_tr16_b64_at<0>(ab);
                 at[c][1] = lds_read_tr16_b64_at<4 * RB>(ab);
@@ -547,7 +556,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             }
         };
         auto wait_a = [&](int c, bool more_in_flight) __attribute__((always_inline)) {
-            if constexpr (XM == kXPlanes) {
+            if constexpr (PLANES) {
                 if (more_in_flight)
                     asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(at[c][0]), "+v"(at[c][1]), "+v"(at[c][2]), "+v"(at[c][3]));
                 else
@@ -609,7 +618,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
             }
             read_a(0, std::integral_constant<int, 0>{});
-            if constexpr (XM == kXPlanes)
+            if constexpr (PLANES)
                 asm volatile("s_waitcnt lgkmcnt(4)"
                              : "+v"(bf[0][0]), "+v"(bf[1][0]), "+v"(bf[2][0]), "+v"(bf[3][0]), "+v"(bf[0][1]), "+v"(bf[1][1]),
                                "+v"(bf[2][1]), "+v"(bf[3][1]));
@@ -829,8 +838,9 @@ bool pipe_applicable(const TileGemmArgs &a, const Layout &L, int xm = kXRows)
     if (B != 8 && B != 16) return false;
     if (L.K % kPanelK != 0 || a.M < 1 || a.M >= (int64_t(1) << 30)) return false;
     if (xm == kXConv) return a.Cin % kPanelK == 0 && uint64_t(a.zero_off) + 128u < (uint64_t(1) << 32);
-    if (xm == kXPlanes)
-        return a.pix % 8 == 0 && a.Cin == L.K && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0 &&
+    if (xm == kXPlanes || xm == kXPlanes2)
+        return a.pix % (xm == kXPlanes ? 8 : 2) == 0 && a.Cin == L.K &&
+               (reinterpret_cast<uintptr_t>(a.X) & (xm == kXPlanes ? 15u : 3u)) == 0 &&
                uint64_t(a.M) * uint64_t(L.K) * 2u < (uint64_t(1) << 32);
     return uint64_t(a.M) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);  // 32-bit DMA offsets
 }
@@ -855,7 +865,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.kp_per = int32_t(kt_per * kTilePanels);
         a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
-        if constexpr (XM == kXPlanes) a.Cin = t.Cin;
+        if constexpr (XM == kXPlanes || XM == kXPlanes2) a.Cin = t.Cin;
         if constexpr (XM == kXConv) {
             a.Cin = t.Cin;
             a.H = t.H;

@@ -283,6 +283,10 @@ CONV_CASES = [
     (2, 320, 16, 16, 200, 1, 1, 0, 8, "bf16"),    # 5 panels, two 256-row tiles, two column tiles
     (1, 2048, 4, 4, 64, 1, 1, 0, 8, "bf16"),      # M = 16, K = 2048: split over K
     (3, 64, 24, 24, 24, 1, 1, 0, 8, "bf16"),      # M = 1728: 128-row tiles (one panel), ragged last tile
+    # the same for an even pixel count that is no multiple of 8 (2-row DMA)
+    (3, 128, 14, 14, 72, 1, 1, 0, 8, "bf16"),     # 196 pixels, M = 588: 128-row tiles (two panels), the last one ragged
+    (2, 64, 5, 2, 24, 1, 1, 0, 16, "bf16"),       # M = 20
+    (4, 320, 6, 3, 136, 1, 1, 0, 8, "bf16"),      # 18 pixels, 5 panels, two column tiles
     # k x k on whole 64-channel panels: the pipelined kernel gathers each panel from the input pixel of its
     # filter tap, or from a page of zeros where the tap falls into the padding
     (2, 64, 9, 10, 40, 3, 1, 1, 8, "bf16"),       # M = 180: the 256-row tile
