@@ -118,6 +118,39 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc_x8(const uint16_t *__restr
     }
 }
 
+// The same copy for small images of any pixel count (P <= kFlatMaxPix) and a multiple of 64 channels: the 64
+// channel planes of a workgroup are one contiguous, 16-byte aligned run of 64 P elements, loaded 16 bytes at a
+// time whatever P is; element e of the run is pixel e % P of channel e / P.
+constexpr int kFlatMaxPix = 256;
+__global__ __launch_bounds__(256) void k_nchw_to_nhwc_flat(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                           int C, int P, uint16_t *zeros)
+{
+    __shared__ uint16_t t[kFlatMaxPix][66];  // [pixel][channel]
+    clear_zero_page(zeros);
+    const int64_t b = blockIdx.y;
+    const int c0 = blockIdx.x * 64;
+    const uint16_t *run = src + (b * C + c0) * int64_t(P);
+    for (int ch = threadIdx.x; ch < 8 * P; ch += 256) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(run + 8 * ch);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        int c = (8 * ch) / P, p = 8 * ch - c * P;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            t[p][c] = uint16_t(w[i >> 1] >> (16 * (i & 1)));
+            if (++p == P) {
+                p = 0;
+                ++c;
+            }
+        }
+    }
+    __syncthreads();
+    const int grp = threadIdx.x & 7;
+    for (int q = threadIdx.x >> 3; q < P; q += 32) {
+        const uint32_t *r = reinterpret_cast<const uint32_t *>(&t[q][8 * grp]);
+        *reinterpret_cast<uint4 *>(dst + (b * int64_t(P) + q) * C + c0 + 8 * grp) = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
 template <int B, int TM, bool CONV>
 __global__ __launch_bounds__(256, 2) void k_tile_gemm_bf16(TileGemmArgs a, Layout L)
 {
@@ -416,6 +449,10 @@ void launch_nchw_to_nhwc(const ConvArgs &c, int Cin, int OH, int OW, int step, v
     const uint16_t *src = static_cast<const uint16_t *>(c.X);
     if (step == 1 && P % 8 == 0 && Cin % 8 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0)
         k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P, zeros);
+    else if (step == 1 && P <= kFlatMaxPix && Cin % 64 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 &&
+             (reinterpret_cast<uintptr_t>(dst) & 15u) == 0)
+        k_nchw_to_nhwc_flat<<<dim3(unsigned(Cin / 64), unsigned(c.Nb)), 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P,
+                                                                                   zeros);
     else
         k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step, zeros);
 }
