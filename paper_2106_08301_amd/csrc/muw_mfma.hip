@@ -14,7 +14,8 @@
 // 8 h .. 8 h + 7 of them), applied identically to both operands.  fp32 accumulation; a launch that would
 // not fill the chip splits K into fp32 partial sums added in split order, so results are bitwise
 // reproducible.  Two workgroups per compute unit hide each other's load/decode phase.  Linear layers with
-// B = 8, 16 and K a multiple of 64 take the software-pipelined kernel of muw_mfma_pipe.hpp instead.
+// B = 8, 16 and K a multiple of 64, and convolutions whose Cin is one, take the software-pipelined kernel of
+// muw_mfma_pipe.hpp instead.
 #include <algorithm>
 #include <type_traits>
 

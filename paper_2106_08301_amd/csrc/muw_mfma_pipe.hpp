@@ -1,7 +1,9 @@
 // muw_mfma_pipe.hpp -- included by muw_mfma.hip (inside its unnamed namespace, after the helpers it uses).
 //
-// Linear layers with K a multiple of 64 and B = 8 or 16: the LDS-tiled MFMA GEMM of muw_mfma.hip, software
-// pipelined (paper Sec. 3.2: the layer is a blocked GEMM whose weight tile is decoded on the fly).
+// Layers with K a multiple of 64 and B = 8 or 16: the LDS-tiled MFMA GEMM of muw_mfma.hip, software
+// pipelined (paper Sec. 3.2: the layer, linear or a convolution, is a blocked GEMM whose weight tile is decoded on
+// the fly).  The activation rows are rows of a matrix, output pixels gathered from an NHWC image (k x k filters),
+// or pixels of NCHW channel planes (1x1 filters; the tile is then k-major and read through the transposing LDS load).
 //   - the activation tile is triple buffered in LDS and filled by global_load_lds two steps ahead;
 //   - the compressed payload of a step is gathered into registers two steps ahead (payload index by
 //     v_mbcnt over the panel masks).  Every wait on the scalar/LDS counter also waits for the scalar loads
