@@ -295,6 +295,12 @@ CONV_CASES = [
     (1, 192, 11, 7, 72, 5, 1, 2, 8, "bf16"),      # 5 x 5, 75 panels split over K: parts start inside a filter row
     (5, 64, 17, 13, 130, 3, 1, 1, 8, "bf16"),     # M = 1105: several row tiles, images straddle them
     (1, 64, 2, 2, 16, 3, 1, 1, 8, "bf16"),        # smaller than the filter: most taps are padding
+    # more than a thousand output pixels: several row tiles in every source mode
+    (6, 128, 14, 14, 72, 1, 1, 0, 8, "bf16"),     # channel planes, 2-row DMA, M = 1176
+    (3, 64, 40, 40, 40, 1, 2, 0, 16, "bf16"),     # strided 1x1: staged rows, M = 1200
+    (2, 64, 24, 24, 40, 3, 1, 1, 4, "bf16"),      # B = 4, M = 1152: the unpipelined kernel's gather
+    (2, 192, 23, 24, 136, 3, 2, 1, 8, "bf16"),    # 3x3 stride 2 on 3 panels per tap, two column tiles, M = 288
+    (9, 128, 12, 12, 200, 3, 1, 1, 16, "bf16"),   # M = 1296, 18 panels
 ]
 
 
