@@ -248,9 +248,12 @@ def report_all(args, torch, muw, synth, to_device):
         _, ms = time_steps(torch, lambda: muw.muw_conv2d(layer, Xd, case.stride, case.pad, out=Y), 30, 10)
         _, ms_torch = time_steps(torch, lambda: torch.nn.functional.conv2d(Xd, Wd, stride=case.stride,
                                                                            padding=case.pad), 30, 10)
+        # the same layer with a bf16 output, which is what the dense library operator beside it writes
+        Yb = torch.empty(Y.shape, dtype=torch.bfloat16, device="cuda")
+        _, ms_b = time_steps(torch, lambda: muw.muw_conv2d(layer, Xd, case.stride, case.pad, out=Yb), 30, 10)
         b = layer.compressed_bytes + Xd.numel() * 2 + Y.numel() * 4
         surv = 2.0 * case.M * case.B * (layer.NB - layer.desc.n_pruned)
-        return {"config": name, "ms": ms, "algorithmic_GBps": b / ms / 1e6,
+        return {"config": name, "ms": ms, "ms_bf16_output": ms_b, "algorithmic_GBps": b / ms / 1e6,
                 "compressed_weight_GBps": layer.compressed_bytes / ms / 1e6, "surviving_TFLOPs": surv / ms / 1e9,
                 "executed_dense_TFLOPs": 2.0 * case.M * case.N * case.K / ms / 1e9,
                 "roofline_frac": _roof(b, surv, ms), "ms_torch_dense": ms_torch, "bytes": b, "surv": surv}
@@ -260,17 +263,19 @@ def report_all(args, torch, muw, synth, to_device):
     r2 = conv_row("cfg2 conv3x3 64->64 b32 @56 B4", synth.config2())
     r2.pop("bytes"), r2.pop("surv")
     rows.append(r2)
-    tot = {"ms": 0.0, "bytes": 0.0, "surv": 0.0, "torch": 0.0, "dense": 0.0}
+    tot = {"ms": 0.0, "ms_b": 0.0, "bytes": 0.0, "surv": 0.0, "torch": 0.0, "dense": 0.0}
     layers3 = []
     for case in synth.config3():
         r = conv_row(case.name, case)
-        layers3.append({k: r[k] for k in ("config", "ms", "algorithmic_GBps", "roofline_frac", "ms_torch_dense")})
+        layers3.append({k: r[k] for k in ("config", "ms", "ms_bf16_output", "algorithmic_GBps", "roofline_frac",
+                                           "ms_torch_dense")})
         tot["ms"] += case.repeat * r["ms"]
+        tot["ms_b"] += case.repeat * r["ms_bf16_output"]
         tot["bytes"] += case.repeat * r["bytes"]
         tot["surv"] += case.repeat * r["surv"]
         tot["torch"] += case.repeat * r["ms_torch_dense"]
         tot["dense"] += case.repeat * 2.0 * case.M * case.N * case.K
-    rows.append({"config": "cfg3 ResNet-50 52 convs b64 B8 (sum)", "ms": tot["ms"],
+    rows.append({"config": "cfg3 ResNet-50 52 convs b64 B8 (sum)", "ms": tot["ms"], "ms_bf16_output": tot["ms_b"],
                  "algorithmic_GBps": tot["bytes"] / tot["ms"] / 1e6, "surviving_TFLOPs": tot["surv"] / tot["ms"] / 1e9,
                  "executed_dense_TFLOPs": tot["dense"] / tot["ms"] / 1e9,
                  "roofline_frac": _roof(tot["bytes"], tot["surv"], tot["ms"]), "ms_torch_dense": tot["torch"],
@@ -299,6 +304,8 @@ def report_all(args, torch, muw, synth, to_device):
     for r in rows:
         log(f"{r['config']:62s} {r['ms']:9.4f} {r['algorithmic_GBps']:8.0f} {r.get('surviving_TFLOPs', 0):8.1f} "
             f"{r.get('executed_dense_TFLOPs', 0):8.1f} {r['roofline_frac']:6.3f} {r['ms_torch_dense']:9.4f}")
+        if "ms_bf16_output" in r:
+            log(f"{'  the same with a bf16 output':62s} {r['ms_bf16_output']:9.4f}")
     return rows
 
 

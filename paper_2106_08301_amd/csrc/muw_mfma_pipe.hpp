@@ -256,6 +256,7 @@ struct PipeArgs {
     int64_t ldx, ldy;
     int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
     int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a convolution's output)
+    int32_t yvec;    // Y (and the partial sums) are 16-byte aligned: NCHW rows may be stored four at a time
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
     // kXConv: X is the input as NHWC [Nb][H][W][Cin], Cin a multiple of 64, M = Nb*OH*OW and
     // k = (kh*KW + kw)*Cin + cin, so a 64-k panel is 128 contiguous bytes of one input pixel -- or of the
@@ -758,8 +759,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                 // for a fixed output channel the lane's 4 rows are 4 consecutive pixels (of one image if
                 // the pixel count is a multiple of 4)
                 const int64_t pix = a.pix;
-                if ((pix & 3) == 0 && mq + 3 < a.M && ydtype == MUW_F32) {
-                    *reinterpret_cast<f32x4 *>(static_cast<float *>(ydst) + (int64_t(img) * L.N + n) * pix + px) = acc[mb][s];
+                if (a.yvec && (pix & 3) == 0 && mq + 3 < a.M) {
+                    const int64_t idx = (int64_t(img) * L.N + n) * pix + px;
+                    if (ydtype == MUW_F32) {
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(ydst) + idx) = acc[mb][s];
+                    } else {
+                        const uint32_t lo = uint32_t(f32_to_bf16_rne(acc[mb][s][0])) | (uint32_t(f32_to_bf16_rne(acc[mb][s][1])) << 16);
+                        const uint32_t hi = uint32_t(f32_to_bf16_rne(acc[mb][s][2])) | (uint32_t(f32_to_bf16_rne(acc[mb][s][3])) << 16);
+                        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(ydst) + idx) = make_uint2(lo, hi);
+                    }
                     continue;
                 }
 #pragma unroll
@@ -867,6 +875,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.kp_per = int32_t(kt_per * kTilePanels);
         a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
+        a.yvec = ((reinterpret_cast<uintptr_t>(t.Y) | reinterpret_cast<uintptr_t>(ws)) & 15u) == 0;
         if constexpr (XM == kXPlanes || XM == kXPlanes2) a.Cin = t.Cin;
         if constexpr (XM == kXConv) {
             a.Cin = t.Cin;

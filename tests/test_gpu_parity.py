@@ -263,6 +263,25 @@ def test_pointwise_conv_bf16_output(muw, oracle):
     check_close(to_f64(Y), Y_ref_b, rel=1e-3, mx=1e-2)
 
 
+@pytest.mark.parametrize("Nb,Cin,H,W,Cout,ks,stride,pad,B", [
+    (2, 64, 9, 10, 40, 3, 1, 1, 8),      # 90 pixels per image: element-wise NCHW stores
+    (3, 64, 24, 24, 24, 1, 1, 0, 8),     # 576 pixels: four pixels of a channel per store
+    (1, 2048, 4, 4, 64, 1, 1, 0, 8),     # split over K: the reduction rounds the sum
+    (2, 128, 12, 12, 72, 3, 2, 1, 16),   # stride 2, 36 pixels
+])
+def test_conv_bf16_output(muw, oracle, Nb, Cin, H, W, Cout, ks, stride, pad, B):
+    case = synth.ConvCase("t", Nb, Cin, H, W, Cout, ks, ks, stride, pad, B, 0.5, 0.4, "bf16", 660 + Cout)
+    X, Wt = synth.make_conv(case)
+    (_, _, _, What), _ = oracle_encode(oracle, Wt, B, 0.5, 0.4)
+    Y_ref = oracle.conv2d(X.f64(), What, ks, ks, stride, pad)
+    layer = muw.muw_encode(to_device(Wt), B, 0.5, 0.4)
+    Y = muw.muw_conv2d(layer, to_device(X), stride, pad, out_dtype=torch.bfloat16)
+    assert Y.dtype == torch.bfloat16
+    # a bf16 output carries its own rounding (relative 2^-9 per element): compare with the reference rounded alike
+    Y_ref_b = synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(Y_ref.astype(np.float32))).reshape(Y_ref.shape)
+    check_close(to_f64(Y), Y_ref_b, rel=1e-3, mx=1e-2)
+
+
 CONV_CASES = [
     # Nb, Cin, H, W, Cout, ks, stride, pad, B, dtype
     (2, 16, 9, 10, 20, 3, 1, 1, 4, "bf16"),
