@@ -178,7 +178,11 @@ muw_status muw_gemm_grouped(const muw_desc *desc, int32_t G, const void *const *
                             const void *const *X_ptrs_dev, muw_dtype xdtype, int64_t M,
                             void *const *Y_ptrs_dev, muw_dtype ydtype, void *hip_stream);
 
-/* Workspace muw_conv2d needs (may be 0).  Host only. */
+/* Workspace muw_conv2d wants (may be 0): room for a channels-last copy of the input (k x k filters, strided or
+ * odd-sized 1x1 layers) and for fp32 partial sums where K is split.  Caller-allocated device memory, contents
+ * undefined on entry and exit.  muw_conv2d returns MUW_ENOSPC if it is given less (or NULL); a workspace that
+ * is not 256-byte aligned (the address torch.empty returns is) is accepted but not used: the general, slower
+ * kernel then computes the same result.  Host only. */
 size_t muw_conv2d_workspace_bytes(const muw_desc *desc, int64_t Nb, int64_t H, int64_t W,
                                   int32_t stride, int32_t pad);
 

@@ -245,7 +245,8 @@ muw_status launch_conv2d(const muw_desc &d, const Layout &L, const ConvArgs &a, 
 {
     const int64_t M = a.Nb * a.OH * a.OW;
     if (M == 0) return MUW_OK;
-    if (tile_conv_applicable(d, L, a) && ws && ws_bytes >= tile_conv_workspace_bytes(d, L, a))
+    if (tile_conv_applicable(d, L, a) && ws && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0 &&
+        ws_bytes >= tile_conv_workspace_bytes(d, L, a))
         return launch_tile_conv(d, L, a, ws, ws_bytes, st);
     ActView av{};
     av.X = a.X;

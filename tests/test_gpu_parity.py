@@ -334,6 +334,35 @@ def test_conv2d_matches_oracle(muw, oracle, Nb, Cin, H, W, Cout, ks, stride, pad
     check_close(to_f64(Y), Y_ref)
 
 
+def test_conv2d_workspace_contract(muw, oracle):
+    """A missing or short workspace is refused before any launch; one that is not 256-byte aligned is accepted and
+    the general kernel computes the same convolution."""
+    import ctypes as C
+    case = synth.ConvCase("t", 2, 64, 9, 10, 40, 3, 3, 1, 1, 8, 0.5, 0.4, "bf16", 671)
+    X, Wt = synth.make_conv(case)
+    (_, _, _, What), _ = oracle_encode(oracle, Wt, 8, 0.5, 0.4)
+    Y_ref = oracle.conv2d(X.f64(), What, 3, 3, 1, 1)
+    layer = muw.muw_encode(to_device(Wt), 8, 0.5, 0.4)
+    Xd = to_device(X)
+    d = layer.desc
+    need = muw.lib.muw_conv2d_workspace_bytes(C.byref(d), 2, 9, 10, 1, 1)
+    assert need > 0
+    buf = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    Y = torch.full((2, 40, 9, 10), float("nan"), dtype=torch.float32, device="cuda")
+
+    def call(ws_ptr, ws_bytes):
+        return muw.lib.muw_conv2d(C.byref(d), layer.blob.data_ptr(), Xd.data_ptr(), muw.MUW_BF16, 2, 9, 10, 1, 1,
+                                  Y.data_ptr(), muw.MUW_F32, ws_ptr, ws_bytes, None)
+
+    assert call(None, 0) == muw.MUW_ENOSPC
+    assert call(buf.data_ptr(), need // 2) == muw.MUW_ENOSPC
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())                  # nothing was launched
+    assert call(buf.data_ptr() + 16, need) == muw.MUW_OK
+    torch.cuda.synchronize()
+    check_close(to_f64(Y), Y_ref)
+
+
 # ---- ADMM steps (Sec. 3.3): bit-exact against the oracle ------------------------------------------
 
 ADMM_CASES = [
