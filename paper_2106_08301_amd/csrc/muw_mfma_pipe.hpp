@@ -770,6 +770,22 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
                     }
                     continue;
                 }
+                if (mq + 3 < a.M && px + 3u < uint32_t(pix)) {
+                    // four pixels of one image, at the element's own alignment only (an odd pixel count, or an
+                    // unaligned Y): still one store (global memory takes unaligned vector accesses)
+                    typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
+                    typedef uint16_t u16x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+                    const int64_t idx = (int64_t(img) * L.N + n) * pix + px;
+                    if (ydtype == MUW_F32) {
+                        *reinterpret_cast<f32x4_a4 *>(static_cast<float *>(ydst) + idx) = acc[mb][s];
+                    } else {
+                        u16x4_a2 o;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[v] = f32_to_bf16_rne(acc[mb][s][v]);
+                        *reinterpret_cast<u16x4_a2 *>(static_cast<uint16_t *>(ydst) + idx) = o;
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     if (mq + v >= a.M) continue;
