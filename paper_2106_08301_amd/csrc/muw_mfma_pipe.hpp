@@ -257,6 +257,12 @@ struct PipeArgs {
     int32_t kp_per;  // split-K: blockIdx.z handles panels [z*kp_per, (z+1)*kp_per)
     int32_t pix;     // 0: Y[M][ldy]; else Y is NCHW [M / pix][N][pix] (a convolution's output)
     int32_t yvec;    // Y (and the partial sums) are 16-byte aligned: NCHW rows may be stored four at a time
+    // The grid is one-dimensional in x: 8 * xcd_chunk workgroups per K part.  Consecutive workgroup ids go to
+    // consecutive XCDs (each with its own L2), so id i is given tile (i % 8) * xcd_chunk + i / 8 of the list that
+    // runs over the nt column tiles of row tile 0, then of row tile 1, ...: the column tiles that share a row tile's
+    // activations meet in one L2.  Ids whose tile is past the end of the list leave at once.  (xcd_chunk = 0: id i is
+    // tile i; with a single column tile there is nothing to share, and the 3x3 layers measured slower regrouped.)
+    int32_t xcd_chunk, nt, n_tiles;
     float *Ypart;    // partial sums [z][M][N] (fp32) when split, else null
     // kXConv: X is the input as NHWC [Nb][H][W][Cin], Cin a multiple of 64, M = Nb*OH*OW and
     // k = (kh*KW + kw)*Cin + cin, so a 64-k panel is 128 contiguous bytes of one input pixel -- or of the
@@ -310,7 +316,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, r = lane & 15, g = lane >> 4;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t m0 = int64_t(blockIdx.y) * TM, n0 = int64_t(blockIdx.x) * kTN;
+    const uint32_t tile_id = a.xcd_chunk ? (blockIdx.x & 7u) * uint32_t(a.xcd_chunk) + (blockIdx.x >> 3) : blockIdx.x;
+    if (tile_id >= uint32_t(a.n_tiles)) return;
+    const uint32_t tile_m = tile_id / uint32_t(a.nt), tile_n = tile_id - tile_m * uint32_t(a.nt);
+    const int64_t m0 = int64_t(tile_m) * TM, n0 = int64_t(tile_n) * kTN;
     const int kp_lo = int(blockIdx.z) * a.kp_per;  // a multiple of the tile length (hence even)
     const int kp_hi = kp_lo + a.kp_per < int(L.KP) ? kp_lo + a.kp_per : int(L.KP);
 
@@ -905,7 +914,10 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
             a.zero_off = uint32_t(t.zero_off);
         }
         const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
-        dim3 grid(nt, unsigned((t.M + tm - 1) / tm), unsigned(splits));
+        a.nt = int32_t(nt);
+        a.n_tiles = int32_t(nt * unsigned((t.M + tm - 1) / tm));
+        a.xcd_chunk = nt > 1 ? (a.n_tiles + 7) / 8 : 0;
+        dim3 grid(unsigned(a.xcd_chunk ? 8 * a.xcd_chunk : a.n_tiles), 1, unsigned(splits));
         if (tm == 256)
             k_pipe_gemm_bf16<B, 8, XM><<<grid, 512, 0, st>>>(a, L);
         else
