@@ -334,6 +334,29 @@ def test_conv2d_matches_oracle(muw, oracle, Nb, Cin, H, W, Cout, ks, stride, pad
     check_close(to_f64(Y), Y_ref)
 
 
+def test_conv2d_seeded_random_shapes(muw, oracle):
+    """Seeded random geometries on whole 64-channel panels: filters 1 .. 5, strides 1 .. 3, padding up to the filter
+    size, odd image sizes, both block lengths -- whichever source mode the launcher picks for them."""
+    rng = np.random.default_rng(20240607)
+    done = 0
+    while done < 14:
+        Nb, Cin = int(rng.integers(1, 5)), 64 * int(rng.integers(1, 4))
+        H, W = int(rng.integers(1, 19)), int(rng.integers(1, 19))
+        ks, stride, pad = int(rng.choice([1, 1, 3, 3, 5])), int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        Cout, B = int(rng.integers(1, 40)) * 8, int(rng.choice([8, 16]))
+        if H + 2 * pad < ks or W + 2 * pad < ks:
+            continue
+        done += 1
+        case = synth.ConvCase("t", Nb, Cin, H, W, Cout, ks, ks, stride, pad, B, 0.5, 0.4, "bf16", 7000 + done)
+        X, Wt = synth.make_conv(case)
+        (_, _, _, What), _ = oracle_encode(oracle, Wt, B, 0.5, 0.4)
+        Y_ref = oracle.conv2d(X.f64(), What, ks, ks, stride, pad)
+        layer = muw.muw_encode(to_device(Wt), B, 0.5, 0.4)
+        Y = muw.muw_conv2d(layer, to_device(X), stride, pad)
+        assert Y.shape == Y_ref.shape, (Nb, Cin, H, W, Cout, ks, stride, pad, B)
+        check_close(to_f64(Y), Y_ref)
+
+
 def test_conv2d_workspace_contract(muw, oracle):
     """A missing or short workspace is refused before any launch; one that is not 256-byte aligned is accepted and
     the general kernel computes the same convolution."""
