@@ -271,6 +271,9 @@ struct PipeArgs {
     // 8 consecutive rows of one k are 16 contiguous bytes.  kXPlanes2: pix even, 2 rows are 4 contiguous bytes.
     int32_t Cin, H, W, OH, OW, KW, stride, pad;
     uint32_t zero_off;
+    // DENSEB instantiation: the layer's weights decoded once to bf16 [N][K] (the caller's workspace); the kernel
+    // then loads its weight tiles by DMA instead of decoding them at every step of every row tile
+    const uint16_t *Wd;
 };
 
 // Where the kernel's activation rows come from.
@@ -295,7 +298,7 @@ __device__ inline u32x2_t lds_read_tr16_b64_at(uint32_t addr)
 // Macro tile TM x 128 x 64, NW waves as NW/2 x 2, wave tile 64 x 64 (TM = 32 NW).  NS = 8 / NW of the
 // eight strips of the tile are a wave's decode duty: with 8 waves the decode of a strip is shared by 256
 // rows of activations.
-template <int B, int NW, int XM>
+template <int B, int NW, int XM, bool DENSEB = false>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
 {
     constexpr int TM = 32 * NW;
@@ -309,7 +312,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     constexpr int NAB = NW == 8 ? 3 : 2;  // activation buffers (three fit only with one workgroup per compute unit)
     constexpr int NMS = 4;             // mask slots
     __shared__ __attribute__((aligned(16))) uint8_t A_lds[NAB][ABYTES];
-    __shared__ __attribute__((aligned(16))) uint4 B_lds[2][kTN * 8];
+    constexpr int NBB = DENSEB ? NAB : 2;  // weight buffers (decoded: one ahead; dense: as far ahead as the activations)
+    constexpr int NBI = 16 / NW;           // DENSEB: weight DMA instructions per wave and step (8 rows of 128 bytes each)
+    __shared__ __attribute__((aligned(16))) uint4 B_lds[NBB][kTN * 8];
     __shared__ __attribute__((aligned(16))) uint8_t M_lds[NW][NMS][NS][32];  // [wave][step % 4][strip]: panel masks
 
     const int tid = threadIdx.x;
@@ -407,6 +412,28 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             for (int i = 0; i < NA; ++i)
                 __builtin_amdgcn_global_load_lds((global_void_t *)(xk + avoff[i]),
                                                  (lds_void_t *)(A_lds[buf] + (wave * NA + i) * 1024), 16, 0, 0);
+        }
+    };
+    // DENSEB: the weight tile is rows n0 .. n0 + 127 of Wd, 64 k of them per step, stored like the decoded tile
+    // (row n: 128 bytes, 16-byte chunks swizzled with the row's key)
+    uint32_t bvoff[NBI];
+    if constexpr (DENSEB) {
+#pragma unroll
+        for (int i = 0; i < NBI; ++i) {
+            const int row = 8 * (wave * NBI + i) + (lane >> 3);
+            const int chunk = (lane & 7) ^ swz_key(row);
+            int64_t n = n0 + row;
+            if (n >= L.N) n = L.N - 1;  // rows past the end compute columns that are never stored
+            bvoff[i] = uint32_t((n * L.K + chunk * 8) * 2);
+        }
+    }
+    auto issue_b = [&](int kp, int buf) {
+        if constexpr (DENSEB) {
+            const uint64_t wk = reinterpret_cast<uint64_t>(a.Wd) + uint64_t(kp) * (kPanelK * 2);
+#pragma unroll
+            for (int i = 0; i < NBI; ++i)
+                __builtin_amdgcn_global_load_lds((global_void_t *)(wk + bvoff[i]),
+                                                 (lds_void_t *)(reinterpret_cast<uint8_t *>(B_lds[buf]) + (wave * NBI + i) * 1024), 16, 0, 0);
         }
     };
     // operand reads: row = 16 x block + r, chunk 2 g + h sits at slot (2 g + h) ^ swz_key(r)
@@ -517,6 +544,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
     // its LDS writes are done; then everyone's.  (With two activation buffers the DMA runs one step
     // ahead only and must land as well: it is issued before the payload loads.)
     auto end_of_step = [&](bool steady) {
+        if constexpr (DENSEB) {
+            // (steady: this step requested the tiles of two steps on, which may stay in flight)
+            if (steady)
+                wait_vmcnt_imm<NA + NBI>();
+            else
+                wait_vmcnt_imm<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            return;
+        }
         if (steady)
             wait_vmcnt_imm<(NAB == 3 ? NA + NS : 0) + NS * kPayloadLoads<B>>();
         else
@@ -585,7 +621,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
 
         // ---- prefetches: activation tile, masks, payload, directory entries
         auto prefetch = [&]() __attribute__((always_inline)) {
-            if constexpr (STEADY) {
+            if constexpr (DENSEB) {
+                if (kp + AHEAD < kp_hi) {
+                    issue_b(kp + AHEAD, abuf_dma);
+                    issue_a(kp + AHEAD, abuf_dma);
+                }
+            } else if constexpr (STEADY) {
                 issue_a(kp + AHEAD, abuf_dma);
                 const int pk = kp + 4 < kp_hi ? kp + 4 : kp + 2;  // (past the K range: any valid panel, never used)
 #pragma unroll
@@ -624,10 +665,18 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         auto read_fragments = [&]() __attribute__((always_inline)) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                bf[0][h] = lds_read_b128_at<PAR * BBYTES + 0 * 2048>(baddr[h]);
-                bf[1][h] = lds_read_b128_at<PAR * BBYTES + 1 * 2048>(baddr[h]);
-                bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
-                bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
+                if constexpr (DENSEB) {
+                    const uint32_t bb = baddr[h] + uint32_t(abuf) * BBYTES;  // (the weight tile shares the activation tile's buffer number)
+                    bf[0][h] = lds_read_b128_at<0 * 2048>(bb);
+                    bf[1][h] = lds_read_b128_at<1 * 2048>(bb);
+                    bf[2][h] = lds_read_b128_at<2 * 2048>(bb);
+                    bf[3][h] = lds_read_b128_at<3 * 2048>(bb);
+                } else {
+                    bf[0][h] = lds_read_b128_at<PAR * BBYTES + 0 * 2048>(baddr[h]);
+                    bf[1][h] = lds_read_b128_at<PAR * BBYTES + 1 * 2048>(baddr[h]);
+                    bf[2][h] = lds_read_b128_at<PAR * BBYTES + 2 * 2048>(baddr[h]);
+                    bf[3][h] = lds_read_b128_at<PAR * BBYTES + 3 * 2048>(baddr[h]);
+                }
             }
             read_a(0, std::integral_constant<int, 0>{});
             if constexpr (PLANES)
@@ -642,7 +691,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
         };
         // ---- decode of the next step's weights into the other buffer
         auto decode_next = [&]() __attribute__((always_inline)) {
-            if (more) {
+            if (!DENSEB && more) {
                 // The payload of step kp + 1 was requested during step kp - 1; since then this wave has issued
                 // at least the activation and mask DMA and the payload loads of this step.
 #pragma unroll
@@ -690,11 +739,24 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(Pip
             mfma_loop();
         }
         abuf = abuf + 1 == NAB ? 0 : abuf + 1;
-        end_of_step(STEADY);
+        if constexpr (DENSEB)
+            end_of_step(AHEAD == 2 && kp + AHEAD < kp_hi);
+        else
+            end_of_step(STEADY);
         TPROF_MARK(4);  // end-of-step waits and barrier
     };
 
-    if (kp_lo < kp_hi) {
+    if (DENSEB && kp_lo < kp_hi) {
+        issue_b(kp_lo, 0);
+        issue_a(kp_lo, 0);
+        if (NAB == 3 && kp_lo + 1 < kp_hi) {
+            issue_b(kp_lo + 1, 1);
+            issue_a(kp_lo + 1, 1);
+        }
+        end_of_step(NAB == 3 && kp_lo + 1 < kp_hi);  // (the tiles of the second step may still be in flight)
+#pragma unroll 1
+        for (int kp = kp_lo; kp < kp_hi; ++kp) step(kp, std::integral_constant<int, 0>{}, std::false_type{}, std::false_type{});
+    } else if (kp_lo < kp_hi) {
         {  // (kp_lo is the first panel of a tile: splits cover whole tiles)
             PanelMasks<B> m0[NS];
             PanelMasks<B>(&m1)[NS] = mset[1];  // (kp_lo is even: the first step decodes with the set of parity 1)
@@ -880,11 +942,13 @@ bool pipe_applicable(const TileGemmArgs &a, const Layout &L, int xm = kXRows)
     return uint64_t(a.M) * uint64_t(a.ldx) * 2u < (uint64_t(1) << 32);  // 32-bit DMA offsets
 }
 
-template <int B, int XM = kXRows>
+template <int B, int XM = kXRows, bool DENSEB = false>
 muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if constexpr (B == 8 || B == 16) {
-        const int tm = int(pipe_tile_rows(L, t.M));
+        // (dense weight tiles: no decode to share among the rows of a tile, and two 128-row workgroups per compute
+        // unit overlap each other's prologue and epilogue)
+        const int tm = DENSEB ? 128 : int(pipe_tile_rows(L, t.M));
         int splits = tile_splits(L, t.M, tm, true);
         if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
         const int64_t kt_per = (L.KT + splits - 1) / splits;
@@ -901,6 +965,7 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.pix = int32_t(t.pix);
         a.Ypart = splits > 1 ? static_cast<float *>(ws) : nullptr;
         a.yvec = ((reinterpret_cast<uintptr_t>(t.Y) | reinterpret_cast<uintptr_t>(ws)) & 15u) == 0;
+        if constexpr (DENSEB) a.Wd = t.Wd;
         if constexpr (XM == kXPlanes || XM == kXPlanes2) a.Cin = t.Cin;
         if constexpr (XM == kXConv) {
             a.Cin = t.Cin;
@@ -919,9 +984,9 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.xcd_chunk = nt > 1 ? (a.n_tiles + 7) / 8 : 0;
         dim3 grid(unsigned(a.xcd_chunk ? 8 * a.xcd_chunk : a.n_tiles), 1, unsigned(splits));
         if (tm == 256)
-            k_pipe_gemm_bf16<B, 8, XM><<<grid, 512, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 8, XM, DENSEB><<<grid, 512, 0, st>>>(a, L);
         else
-            k_pipe_gemm_bf16<B, 4, XM><<<grid, 256, 0, st>>>(a, L);
+            k_pipe_gemm_bf16<B, 4, XM, DENSEB><<<grid, 256, 0, st>>>(a, L);
         if (splits > 1) {
             const int64_t total = t.M * L.N;
             if (t.pix || t.ldy == L.N)
