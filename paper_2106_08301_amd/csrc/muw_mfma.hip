@@ -502,14 +502,14 @@ size_t tile_conv_zero_off(const muw_desc &d, const ConvArgs &a)
 }
 size_t tile_conv_nhwc_bytes(const muw_desc &d, const ConvArgs &a) { return tile_conv_zero_off(d, a) + 256u; }
 
-// A k x k convolution with many more output pixels than output channels (at least 32 times) and whole panels:
-// the layer is decoded once per call to bf16 [N][K] in the workspace and every row tile loads its weight tiles
-// from there, instead of decoding them again at each of its steps.  (Measured on the ResNet-50 shapes: a gain
-// where this holds, a loss for 1x1 filters, whose kernels are bound by HBM, and for the 512-channel layers.)
+// A convolution with many more output pixels than output channels (at least 32 times) and whole panels: the
+// layer is decoded once per call to bf16 [N][K] in the workspace and every row tile loads its weight tiles from
+// there, instead of decoding them again at each of its steps.  (Measured on the ResNet-50 shapes: 4-13 us off the
+// 3x3 layers and 2-9 us off most 1x1 layers where this holds, a loss of 2-4 us where it does not.)
 size_t conv_dense_weight_bytes(const muw_desc &d, const Layout &L, const ConvArgs &a)
 {
     const int64_t M = a.Nb * a.OH * a.OW;
-    if (d.wdtype != MUW_BF16 || d.KH * d.KW == 1 || d.Cin % kPanelK != 0 || M < 32 * L.N) return 0;
+    if (d.wdtype != MUW_BF16 || d.Cin % kPanelK != 0 || M < 32 * L.N) return 0;
     if (d.B != 4 && d.B != 8 && d.B != 16) return 0;
     return size_t((uint64_t(L.N) * uint64_t(L.K) * 2u + 255u) & ~uint64_t(255));
 }
@@ -522,6 +522,17 @@ size_t tile_conv_part_bytes(const Layout &L, const ConvArgs &a)
 size_t tile_conv_workspace_bytes(const muw_desc &d, const Layout &L, const ConvArgs &a)
 {
     return tile_conv_nhwc_bytes(d, a) + tile_conv_part_bytes(L, a) + conv_dense_weight_bytes(d, L, a);
+}
+
+// Launch of the decode-once pass into w (conv_dense_weight_bytes of the workspace).
+static uint16_t *decode_dense_weights(const muw_desc &d, const Layout &L, const ConvArgs &c, void *w, hipStream_t st)
+{
+    uint16_t *Wd = static_cast<uint16_t *>(w);
+    const unsigned tiles = unsigned(L.NT);
+    if (d.B == 4) k_decode_panels_bf16<4><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
+    if (d.B == 8) k_decode_panels_bf16<8><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
+    if (d.B == 16) k_decode_panels_bf16<16><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
+    return Wd;
 }
 
 muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &c, void *ws, size_t ws_bytes,
@@ -542,9 +553,13 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         a.ydtype = c.ydtype;
         a.pix = P;
         a.Cin = d.Cin;
+        const bool dense = conv_dense_weight_bytes(d, L, c) != 0 && L.K % kPanelK == 0;
+        if (dense) a.Wd = decode_dense_weights(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes, st);
         if (c.stride == 1) {
             // every pixel is read: the pipelined kernel takes the channel planes as they are
             a.X = static_cast<const uint16_t *>(c.X);
+            if (dense && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes, true>(a, L, part, part_bytes, st);
+            if (dense && pipe_applicable<8>(a, L, kXPlanes2)) return launch_pipe<8, kXPlanes2, true>(a, L, part, part_bytes, st);
             if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes>(a, L, part, part_bytes, st);
             if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes)) return launch_pipe<16, kXPlanes>(a, L, part, part_bytes, st);
             if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes2)) return launch_pipe<8, kXPlanes2>(a, L, part, part_bytes, st);
@@ -552,6 +567,7 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         }
         launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
         a.X = static_cast<const uint16_t *>(ws);
+        if (dense && pipe_applicable<8>(a, L)) return launch_pipe<8, kXRows, true>(a, L, part, part_bytes, st);
         switch (d.B) {
         case 8:
             if (pipe_applicable<8>(a, L)) return launch_pipe<8>(a, L, part, part_bytes, st);
@@ -585,12 +601,7 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         p.ldy = L.N;
         p.pix = c.OH * c.OW;
         if (conv_dense_weight_bytes(d, L, c) && pipe_applicable<8>(p, L, kXConv)) {
-            uint16_t *Wd = reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(ws) + nhwc + part_bytes);
-            const unsigned tiles = unsigned(L.NT);
-            if (d.B == 4) k_decode_panels_bf16<4><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-            if (d.B == 8) k_decode_panels_bf16<8><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-            if (d.B == 16) k_decode_panels_bf16<16><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-            p.Wd = Wd;
+            p.Wd = decode_dense_weights(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes, st);
             return launch_pipe<8, kXConv, true>(p, L, part, part_bytes, st);
         }
         if (d.B == 8 && pipe_applicable<8>(p, L, kXConv)) return launch_pipe<8, kXConv>(p, L, part, part_bytes, st);

@@ -320,12 +320,15 @@ CONV_CASES = [
     (2, 64, 24, 24, 40, 3, 1, 1, 4, "bf16"),      # B = 4, M = 1152: the unpipelined kernel's gather
     (2, 192, 23, 24, 136, 3, 2, 1, 8, "bf16"),    # 3x3 stride 2 on 3 panels per tap, two column tiles, M = 288
     (9, 128, 12, 12, 200, 3, 1, 1, 16, "bf16"),   # M = 1296, 18 panels
-    # k x k with at least 32 output pixels per output channel: the layer is decoded once per call and the kernel
-    # loads dense weight tiles
+    # at least 32 output pixels per output channel: the layer is decoded once per call and the kernel loads dense
+    # weight tiles
     (2, 64, 24, 24, 24, 3, 1, 1, 4, "bf16"),      # B = 4, M = 1152
     (3, 128, 40, 40, 32, 3, 2, 1, 8, "bf16"),     # stride 2, M = 1200, two panels per tap
     (1, 64, 33, 35, 16, 5, 1, 2, 16, "bf16"),     # 5 x 5, M = 1155 (ragged row tile), 25 panels
     (2, 192, 9, 9, 8, 3, 1, 0, 8, "bf16"),        # M = 98 (one ragged tile), 27 panels, 8 output channels
+    (6, 128, 14, 14, 32, 1, 1, 0, 8, "bf16"),     # the same rule for 1x1 filters: channel planes, 2-row DMA
+    (3, 64, 40, 40, 32, 1, 2, 0, 16, "bf16"),     # strided 1x1: staged rows
+    (2, 128, 32, 32, 56, 1, 1, 0, 16, "bf16"),    # channel planes, 8-row DMA, M = 2048
 ]
 
 
