@@ -510,6 +510,7 @@ size_t conv_dense_weight_bytes(const muw_desc &d, const Layout &L, const ConvArg
 {
     const int64_t M = a.Nb * a.OH * a.OW;
     if (d.wdtype != MUW_BF16 || d.Cin % kPanelK != 0 || M < 32 * L.N) return 0;
+    if (uint64_t(L.N) * uint64_t(L.K) * 2u >= (uint64_t(1) << 32)) return 0;  // 32-bit DMA offsets into the decoded layer
     if (d.B != 4 && d.B != 8 && d.B != 16) return 0;
     return size_t((uint64_t(L.N) * uint64_t(L.K) * 2u + 255u) & ~uint64_t(255));
 }
