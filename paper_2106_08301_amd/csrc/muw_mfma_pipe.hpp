@@ -983,10 +983,14 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
         a.n_tiles = int32_t(nt * unsigned((t.M + tm - 1) / tm));
         a.xcd_chunk = nt > 1 ? (a.n_tiles + 7) / 8 : 0;
         dim3 grid(unsigned(a.xcd_chunk ? 8 * a.xcd_chunk : a.n_tiles), 1, unsigned(splits));
-        if (tm == 256)
-            k_pipe_gemm_bf16<B, 8, XM, DENSEB><<<grid, 512, 0, st>>>(a, L);
-        else
-            k_pipe_gemm_bf16<B, 4, XM, DENSEB><<<grid, 256, 0, st>>>(a, L);
+        if constexpr (DENSEB) {
+            k_pipe_gemm_bf16<B, 4, XM, true><<<grid, 256, 0, st>>>(a, L);  // (always 128-row tiles)
+        } else {
+            if (tm == 256)
+                k_pipe_gemm_bf16<B, 8, XM, false><<<grid, 512, 0, st>>>(a, L);
+            else
+                k_pipe_gemm_bf16<B, 4, XM, false><<<grid, 256, 0, st>>>(a, L);
+        }
         if (splits > 1) {
             const int64_t total = t.M * L.N;
             if (t.pix || t.ldy == L.N)
