@@ -58,6 +58,57 @@ struct TileGemmArgs {
 __device__ inline int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 __device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ swz_key(row)); }
 
+// The whole layer decoded to bf16 [N][K] (K a whole number of panels): one wavefront per panel of a tile, each
+// lane writes its 16 weights (row lane % 16, k = 16 (lane / 16) .. + 15 of the panel) with two 16-byte stores.
+// A workgroup of 256 threads decodes one tile.
+template <int B>
+__device__ inline void decode_tile_bf16(const uint8_t *__restrict__ blob, const Layout &L, uint16_t *__restrict__ Wd, int64_t tile)
+{
+    constexpr int S = 16 / B;
+    const int p = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const int64_t strip = tile / L.KT, kt = tile % L.KT;
+    const int np = panels_in_tile(L, kt);
+    if (p >= np) return;
+    const DirEntry de = reinterpret_cast<const DirEntry *>(blob + L.dir_off)[tile];
+    const uint8_t *base = blob + L.streams_off + uint64_t(de.off16) * 16;
+    const TileStreams ts = tile_streams(B, 2, np, de.nU, de.nD);
+    // payload ranks of the panels before this one
+    const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
+    uint32_t ru = 0, rd = 0;
+    for (int q = 0; q < p; ++q)
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            ru += uint32_t(__popcll(masks[q * 2 * S + j]));
+            rd += uint32_t(__popcll(masks[q * 2 * S + S + j]));
+        }
+    uint32_t w[8];
+    decode_panel_bf16<B>(base, ts, p, ru, rd, lane, w);
+    const int64_t n = strip * kStripRows + r;
+    if (n >= L.N) return;
+    uint4 *dst = reinterpret_cast<uint4 *>(Wd + n * L.K + (kt * kTilePanels + p) * kPanelK + 16 * g);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+}
+
+// That pass as a job: its own launch (k_decode_layer_bf16), or extra workgroups of the staging copy that precedes
+// the same GEMM, so that the two short, latency-bound passes run side by side.  blob = null: no job.
+struct DecodeJob {
+    const uint8_t *blob;
+    uint16_t *Wd;
+    Layout L;
+    int32_t B;
+};
+// Workgroup `first` of `count` takes tiles first, first + count, ...
+__device__ inline void run_decode_job(const DecodeJob &j, int64_t first, int64_t count)
+{
+    for (int64_t tile = first; tile < j.L.NT; tile += count) {
+        if (j.B == 4) decode_tile_bf16<4>(j.blob, j.L, j.Wd, tile);
+        if (j.B == 8) decode_tile_bf16<8>(j.blob, j.L, j.Wd, tile);
+        if (j.B == 16) decode_tile_bf16<16>(j.blob, j.L, j.Wd, tile);
+    }
+}
+__global__ __launch_bounds__(256) void k_decode_layer_bf16(DecodeJob j) { run_decode_job(j, blockIdx.x, gridDim.x); }
+
 // NCHW -> NHWC copy of a bf16 tensor (64 channels x 64 pixels per workgroup through LDS), so that the
 // implicit-GEMM A operand (8 consecutive input channels of one pixel) is one 16-byte load.  With
 // step > 1 only every step-th pixel of every step-th row is taken (OH x OW of them): the input of a
@@ -69,10 +120,18 @@ __device__ inline void clear_zero_page(uint16_t *zeros)
         reinterpret_cast<uint4 *>(zeros)[threadIdx.x] = make_uint4(0, 0, 0, 0);
 }
 
+// The workgroups of the slices past the last image (blockIdx.z >= nb; blockIdx.y >= nb for the flat copy) run the
+// decode job instead, if there is one: enough slices for one tile per workgroup, 64 at most.
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                      int C, int H, int W, int OH, int OW, int step, uint16_t *zeros)
+                                                      int C, int H, int W, int OH, int OW, int step, uint16_t *zeros,
+                                                      int nb, DecodeJob job)
 {
     __shared__ uint16_t t[64][66];
+    if (int(blockIdx.z) >= nb) {
+        run_decode_job(job, (int64_t(blockIdx.z - nb) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x,
+                       int64_t(gridDim.x) * gridDim.y * (gridDim.z - nb));
+        return;
+    }
     clear_zero_page(zeros);
     const int64_t b = blockIdx.z;
     const int P = OH * OW;
@@ -95,9 +154,14 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict
 // aligned rows on both sides): 16-byte global loads (8 pixels of a channel) and stores (8 channels of a
 // pixel); the transposition happens in LDS, written 2 bytes at a time and read back as dwords.
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc_x8(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                         int C, int P, uint16_t *zeros)
+                                                         int C, int P, uint16_t *zeros, int nb, DecodeJob job)
 {
     __shared__ uint16_t t[64][66];  // [pixel][channel]; 33-dword rows spread the 2-byte writes over the banks
+    if (int(blockIdx.z) >= nb) {
+        run_decode_job(job, (int64_t(blockIdx.z - nb) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x,
+                       int64_t(gridDim.x) * gridDim.y * (gridDim.z - nb));
+        return;
+    }
     clear_zero_page(zeros);
     const int64_t b = blockIdx.z;
     const int c0 = blockIdx.y * 64, p0 = blockIdx.x * 64;
@@ -126,9 +190,13 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc_x8(const uint16_t *__restr
 // time whatever P is; element e of the run is pixel e % P of channel e / P.
 constexpr int kFlatMaxPix = 256;
 __global__ __launch_bounds__(256) void k_nchw_to_nhwc_flat(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                           int C, int P, uint16_t *zeros)
+                                                           int C, int P, uint16_t *zeros, int nb, DecodeJob job)
 {
     __shared__ uint16_t t[kFlatMaxPix][66];  // [pixel][channel]
+    if (int(blockIdx.y) >= nb) {
+        run_decode_job(job, int64_t(blockIdx.y - nb) * gridDim.x + blockIdx.x, int64_t(gridDim.x) * (gridDim.y - nb));
+        return;
+    }
     clear_zero_page(zeros);
     const int64_t b = blockIdx.y;
     const int c0 = blockIdx.x * 64;
@@ -152,38 +220,6 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc_flat(const uint16_t *__res
         const uint32_t *r = reinterpret_cast<const uint32_t *>(&t[q][8 * grp]);
         *reinterpret_cast<uint4 *>(dst + (b * int64_t(P) + q) * C + c0 + 8 * grp) = make_uint4(r[0], r[1], r[2], r[3]);
     }
-}
-
-// The whole layer decoded to bf16 [N][K] (K a whole number of panels): one wavefront per panel of a tile, each
-// lane writes its 16 weights (row lane % 16, k = 16 (lane / 16) .. + 15 of the panel) with two 16-byte stores.
-template <int B>
-__global__ __launch_bounds__(256) void k_decode_panels_bf16(const uint8_t *__restrict__ blob, Layout L, uint16_t *__restrict__ Wd)
-{
-    constexpr int S = 16 / B;
-    const int64_t tile = blockIdx.x;
-    const int p = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
-    const int64_t strip = tile / L.KT, kt = tile % L.KT;
-    const int np = panels_in_tile(L, kt);
-    if (p >= np) return;
-    const DirEntry de = reinterpret_cast<const DirEntry *>(blob + L.dir_off)[tile];
-    const uint8_t *base = blob + L.streams_off + uint64_t(de.off16) * 16;
-    const TileStreams ts = tile_streams(B, 2, np, de.nU, de.nD);
-    // payload ranks of the panels before this one
-    const uint64_t *masks = reinterpret_cast<const uint64_t *>(base);
-    uint32_t ru = 0, rd = 0;
-    for (int q = 0; q < p; ++q)
-#pragma unroll
-        for (int j = 0; j < S; ++j) {
-            ru += uint32_t(__popcll(masks[q * 2 * S + j]));
-            rd += uint32_t(__popcll(masks[q * 2 * S + S + j]));
-        }
-    uint32_t w[8];
-    decode_panel_bf16<B>(base, ts, p, ru, rd, lane, w);
-    const int64_t n = strip * kStripRows + r;
-    if (n >= L.N) return;
-    uint4 *dst = reinterpret_cast<uint4 *>(Wd + n * L.K + (kt * kTilePanels + p) * kPanelK + 16 * g);
-    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
 }
 
 template <int B, int TM, bool CONV>
@@ -470,26 +506,36 @@ bool tile_conv_applicable(const muw_desc &d, const Layout &, const ConvArgs &a)
 {
     if (d.wdtype != MUW_BF16 || d.Cin % 8 != 0) return false;
     if (a.Nb * a.H * a.W >= (int64_t(1) << 31) || a.H >= 32768 || a.W >= 32768) return false;
-    if (a.Nb > 65535 || (a.Nb * a.OH * a.OW + 127) / 128 > 65535) return false;
+    if (a.Nb >= 65535 - 64 || (a.Nb * a.OH * a.OW + 127) / 128 > 65535) return false;  // (grid z: the images and up to 64 more slices)
     if ((reinterpret_cast<uintptr_t>(a.X) & 1u)) return false;
     return true;
 }
 
 // NCHW -> NHWC staging of the input (step > 1: only the pixels a strided 1x1 convolution reads)
+// (job: a decode-once pass to run beside the copy, or null)
 void launch_nchw_to_nhwc(const ConvArgs &c, int Cin, int OH, int OW, int step, void *dst, hipStream_t st,
-                         uint16_t *zeros = nullptr)
+                         uint16_t *zeros = nullptr, const DecodeJob *job = nullptr)
 {
     const int P = OH * OW;
-    dim3 tg(unsigned((P + 63) / 64), unsigned((Cin + 63) / 64), unsigned(c.Nb));
+    const int nb = int(c.Nb);
+    DecodeJob j{};
+    if (job) j = *job;
+    auto slices = [&](int64_t per_slice) -> unsigned {
+        if (!job) return 0u;
+        const int64_t n = (j.L.NT + per_slice - 1) / per_slice;
+        return unsigned(n < 1 ? 1 : n > 64 ? 64 : n);
+    };
+    const int64_t gx = (P + 63) / 64, gy = (Cin + 63) / 64;
+    dim3 tg(unsigned(gx), unsigned(gy), unsigned(nb) + slices(gx * gy));
     const uint16_t *src = static_cast<const uint16_t *>(c.X);
     if (step == 1 && P % 8 == 0 && Cin % 8 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0)
-        k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P, zeros);
+        k_nchw_to_nhwc_x8<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P, zeros, nb, j);
     else if (step == 1 && P <= kFlatMaxPix && Cin % 64 == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 &&
              (reinterpret_cast<uintptr_t>(dst) & 15u) == 0)
-        k_nchw_to_nhwc_flat<<<dim3(unsigned(Cin / 64), unsigned(c.Nb)), 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, P,
-                                                                                   zeros);
+        k_nchw_to_nhwc_flat<<<dim3(unsigned(Cin / 64), unsigned(nb) + slices(Cin / 64)), 256, 0, st>>>(
+            src, static_cast<uint16_t *>(dst), Cin, P, zeros, nb, j);
     else
-        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step, zeros);
+        k_nchw_to_nhwc<<<tg, 256, 0, st>>>(src, static_cast<uint16_t *>(dst), Cin, int(c.H), int(c.W), OH, OW, step, zeros, nb, j);
 }
 
 // 1x1, no padding (any stride): every output pixel reads exactly one input pixel
@@ -525,15 +571,19 @@ size_t tile_conv_workspace_bytes(const muw_desc &d, const Layout &L, const ConvA
     return tile_conv_nhwc_bytes(d, a) + tile_conv_part_bytes(L, a) + conv_dense_weight_bytes(d, L, a);
 }
 
-// Launch of the decode-once pass into w (conv_dense_weight_bytes of the workspace).
-static uint16_t *decode_dense_weights(const muw_desc &d, const Layout &L, const ConvArgs &c, void *w, hipStream_t st)
+// The decode-once pass into w (conv_dense_weight_bytes of the workspace), and its launch on its own.
+static DecodeJob dense_weights_job(const muw_desc &d, const Layout &L, const ConvArgs &c, void *w)
 {
-    uint16_t *Wd = static_cast<uint16_t *>(w);
-    const unsigned tiles = unsigned(L.NT);
-    if (d.B == 4) k_decode_panels_bf16<4><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-    if (d.B == 8) k_decode_panels_bf16<8><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-    if (d.B == 16) k_decode_panels_bf16<16><<<tiles, 256, 0, st>>>(static_cast<const uint8_t *>(c.blob), L, Wd);
-    return Wd;
+    DecodeJob j{};
+    j.blob = static_cast<const uint8_t *>(c.blob);
+    j.Wd = static_cast<uint16_t *>(w);
+    j.L = L;
+    j.B = d.B;
+    return j;
+}
+static void launch_decode_job(const DecodeJob &j, hipStream_t st)
+{
+    k_decode_layer_bf16<<<unsigned(j.L.NT < 65536 ? j.L.NT : 65536), 256, 0, st>>>(j);
 }
 
 muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &c, void *ws, size_t ws_bytes,
@@ -555,20 +605,28 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         a.pix = P;
         a.Cin = d.Cin;
         const bool dense = conv_dense_weight_bytes(d, L, c) != 0 && L.K % kPanelK == 0;
-        if (dense) a.Wd = decode_dense_weights(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes, st);
+        const DecodeJob job = dense_weights_job(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes);
+        if (dense) a.Wd = job.Wd;
         if (c.stride == 1) {
             // every pixel is read: the pipelined kernel takes the channel planes as they are
             a.X = static_cast<const uint16_t *>(c.X);
-            if (dense && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes, true>(a, L, part, part_bytes, st);
-            if (dense && pipe_applicable<8>(a, L, kXPlanes2)) return launch_pipe<8, kXPlanes2, true>(a, L, part, part_bytes, st);
+            if (dense && pipe_applicable<8>(a, L, kXPlanes)) {
+                launch_decode_job(job, st);
+                return launch_pipe<8, kXPlanes, true>(a, L, part, part_bytes, st);
+            }
+            if (dense && pipe_applicable<8>(a, L, kXPlanes2)) {
+                launch_decode_job(job, st);
+                return launch_pipe<8, kXPlanes2, true>(a, L, part, part_bytes, st);
+            }
             if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes)) return launch_pipe<8, kXPlanes>(a, L, part, part_bytes, st);
             if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes)) return launch_pipe<16, kXPlanes>(a, L, part, part_bytes, st);
             if (d.B == 8 && pipe_applicable<8>(a, L, kXPlanes2)) return launch_pipe<8, kXPlanes2>(a, L, part, part_bytes, st);
             if (d.B == 16 && pipe_applicable<16>(a, L, kXPlanes2)) return launch_pipe<16, kXPlanes2>(a, L, part, part_bytes, st);
         }
-        launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st);
         a.X = static_cast<const uint16_t *>(ws);
-        if (dense && pipe_applicable<8>(a, L)) return launch_pipe<8, kXRows, true>(a, L, part, part_bytes, st);
+        const bool dense_rows = dense && pipe_applicable<8>(a, L);
+        launch_nchw_to_nhwc(c, d.Cin, int(c.OH), int(c.OW), c.stride, ws, st, nullptr, dense_rows ? &job : nullptr);
+        if (dense_rows) return launch_pipe<8, kXRows, true>(a, L, part, part_bytes, st);
         switch (d.B) {
         case 8:
             if (pipe_applicable<8>(a, L)) return launch_pipe<8>(a, L, part, part_bytes, st);
@@ -580,7 +638,6 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
         }
     }
     const size_t zero_off = tile_conv_zero_off(d, c);
-    launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st, reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(ws) + zero_off));
     TileGemmArgs a{};
     a.blob = static_cast<const uint8_t *>(c.blob);
     a.X = static_cast<const uint16_t *>(ws);
@@ -596,15 +653,19 @@ muw_status launch_tile_conv(const muw_desc &d, const Layout &L, const ConvArgs &
     a.stride = c.stride;
     a.pad = c.pad;
     a.zero_off = int64_t(zero_off);
+    uint16_t *zero_page = reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(ws) + zero_off);
     {
         // whole 64-channel panels: the pipelined kernel gathers them pixel by pixel
         TileGemmArgs p = a;
         p.ldy = L.N;
         p.pix = c.OH * c.OW;
         if (conv_dense_weight_bytes(d, L, c) && pipe_applicable<8>(p, L, kXConv)) {
-            p.Wd = decode_dense_weights(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes, st);
+            const DecodeJob job = dense_weights_job(d, L, c, static_cast<uint8_t *>(ws) + nhwc + part_bytes);
+            launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st, zero_page, &job);
+            p.Wd = job.Wd;
             return launch_pipe<8, kXConv, true>(p, L, part, part_bytes, st);
         }
+        launch_nchw_to_nhwc(c, d.Cin, int(c.H), int(c.W), 1, ws, st, zero_page);
         if (d.B == 8 && pipe_applicable<8>(p, L, kXConv)) return launch_pipe<8, kXConv>(p, L, part, part_bytes, st);
         if (d.B == 16 && pipe_applicable<16>(p, L, kXConv)) return launch_pipe<16, kXConv>(p, L, part, part_bytes, st);
     }
