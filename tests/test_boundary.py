@@ -84,3 +84,21 @@ def test_bad_arguments_are_rejected_on_the_host(muw):
     assert c2(C.byref(cv), fake, fake, muw.MUW_BF16, 2, 8, 8, 0, 1, fake, muw.MUW_F32, None, 0, None) == muw.MUW_EINVAL
     assert c2(C.byref(cv), fake, fake, muw.MUW_BF16, 2, 1, 1, 1, 0, fake, muw.MUW_F32, None, 0, None) == muw.MUW_ESHAPE
     assert c2(C.byref(cv), fake, None, muw.MUW_BF16, 2, 8, 8, 1, 1, fake, muw.MUW_F32, None, 0, None) == muw.MUW_EINVAL
+
+
+def test_conv_workspace_sizes(muw):
+    """Host-only sizing of the convolution workspace: the channels-last copy of the input and its zero page, room
+    for K-split partial sums, and the decoded layer where there are at least 32 output pixels per output channel."""
+    q = muw.lib.muw_conv2d_workspace_bytes
+    cv = muw.make_desc(64, 64 * 9, 8, muw.MUW_BF16, 3, 3, 64)           # 3x3, 64 -> 64
+    nhwc = lambda nb, h, w, cin: nb * h * w * cin * 2
+    few = q(C.byref(cv), 2, 8, 8, 1, 1)                                  # 128 output pixels: no decoded layer
+    assert nhwc(2, 8, 8, 64) + 256 <= few < nhwc(2, 8, 8, 64) + 256 + 64 * 576 * 2 + 16 * 128 * 64 * 4
+    many = q(C.byref(cv), 32, 56, 56, 1, 1)                              # 100352 output pixels: decoded layer too
+    assert many >= nhwc(32, 56, 56, 64) + 256 + 64 * 576 * 2
+    assert many < nhwc(32, 56, 56, 64) + 256 + 64 * 576 * 2 + 4096       # no K split on a grid this large
+    # a missing workspace is refused on the host
+    fake = C.c_void_p(0x1000)
+    assert muw.lib.muw_conv2d(C.byref(cv), fake, fake, muw.MUW_BF16, 32, 56, 56, 1, 1, fake, muw.MUW_F32, None, 0,
+                              None) == muw.MUW_ENOSPC
+    assert q(C.byref(cv), 2, 1, 1, 1, 0) == 0                            # no output pixel (3x3 on 1x1 without padding)
