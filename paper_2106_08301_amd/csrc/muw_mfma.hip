@@ -139,14 +139,28 @@ __global__ __launch_bounds__(256) void k_nchw_to_nhwc(const uint16_t *__restrict
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int p = p0 + tx;
     const int64_t sp = step == 1 ? p : int64_t(p / OW) * step * W + int64_t(p % OW) * step;  // source pixel
+    // t is [pixel][channel]: 33-dword rows spread the 2-byte writes of 64 pixels over the banks
+#pragma unroll 4
     for (int i = ty; i < 64; i += 4) {
         const int c = c0 + i;
-        t[i][tx] = (c < C && p < P) ? src[(b * C + c) * (int64_t(H) * W) + sp] : uint16_t(0);
+        t[tx][i] = (c < C && p < P) ? src[(b * C + c) * (int64_t(H) * W) + sp] : uint16_t(0);
     }
     __syncthreads();
+    if ((C & 7) == 0 && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        // 8 channels of a pixel per 16-byte store
+        const int grp = threadIdx.x & 7, row = threadIdx.x >> 3;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int q = p0 + row + 32 * half, cg = c0 + 8 * grp;
+            if (q >= P || cg >= C) continue;
+            const uint32_t *r = reinterpret_cast<const uint32_t *>(&t[row + 32 * half][8 * grp]);
+            *reinterpret_cast<uint4 *>(dst + (b * P + q) * C + cg) = make_uint4(r[0], r[1], r[2], r[3]);
+        }
+        return;
+    }
     for (int i = ty; i < 64; i += 4) {
         const int q = p0 + i, c = c0 + tx;
-        if (q < P && c < C) dst[(b * P + q) * C + c] = t[tx][i];
+        if (q < P && c < C) dst[(b * P + q) * C + c] = t[i][tx];
     }
 }
 
