@@ -298,33 +298,37 @@ __device__ inline u32x2_t lds_read_tr16_b64_at(uint32_t addr)
 // Macro tile TM x 128 x 64, NW waves as NW/2 x 2, wave tile 64 x 64 (TM = 32 NW).  NS = 8 / NW of the
 // eight strips of the tile are a wave's decode duty: with 8 waves the decode of a strip is shared by 256
 // rows of activations.
-template <int B, int NW, int XM, bool DENSEB = false>
+// WN = 1 (dense weight tiles, layers of at most 64 output channels): the waves form a column, NW x 1, and the macro
+// tile is 64 NW x 64 x 64 -- no half of the matrix instructions spent on columns that do not exist.
+template <int B, int NW, int XM, bool DENSEB = false, int WN = 2>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void k_pipe_gemm_bf16(PipeArgs a, Layout L)
 {
-    constexpr int TM = 32 * NW;
+    static_assert(WN == 2 || (WN == 1 && NW == 4 && DENSEB), "the one-column wave grid exists for the 4-wave dense build");
+    constexpr int TM = (64 / WN) * NW;
+    constexpr int TN = 64 * WN;
     constexpr int NS = 8 / NW;         // strips decoded by a wave
     constexpr int MB = 4;              // 16-row blocks per wave
     constexpr bool PLANES = XM == kXPlanes || XM == kXPlanes2;
     constexpr int DW = XM == kXPlanes2 ? 4 : 16;  // bytes a lane moves per activation DMA instruction
-    constexpr int NA = 64 / DW;        // activation DMA instructions per wave and step (64 DW bytes each; 4: 8 rows of 128 bytes)
+    constexpr int NA = (TM / (8 * NW)) * (16 / DW);  // activation DMA instructions per wave and step (64 DW bytes each; 16-byte DMA: 8 rows of 128 bytes)
     constexpr int ABYTES = TM * 128;   // one activation buffer
-    constexpr int BBYTES = kTN * 128;  // one weight buffer
+    constexpr int BBYTES = TN * 128;   // one weight buffer
     constexpr int NAB = NW == 8 ? 3 : 2;  // activation buffers (three fit only with one workgroup per compute unit)
     constexpr int NMS = 4;             // mask slots
     __shared__ __attribute__((aligned(16))) uint8_t A_lds[NAB][ABYTES];
     constexpr int NBB = DENSEB ? NAB : 2;  // weight buffers (decoded: one ahead; dense: as far ahead as the activations)
-    constexpr int NBI = 16 / NW;           // DENSEB: weight DMA instructions per wave and step (8 rows of 128 bytes each)
-    __shared__ __attribute__((aligned(16))) uint4 B_lds[NBB][kTN * 8];
+    constexpr int NBI = TN / (8 * NW);     // DENSEB: weight DMA instructions per wave and step (8 rows of 128 bytes each)
+    __shared__ __attribute__((aligned(16))) uint4 B_lds[NBB][TN * 8];
     __shared__ __attribute__((aligned(16))) uint8_t M_lds[NW][NMS][NS][32];  // [wave][step % 4][strip]: panel masks
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = WN == 2 ? wave >> 1 : wave, wn = WN == 2 ? wave & 1 : 0;
     const uint32_t tile_id = a.xcd_chunk ? (blockIdx.x & 7u) * uint32_t(a.xcd_chunk) + (blockIdx.x >> 3) : blockIdx.x;
     if (tile_id >= uint32_t(a.n_tiles)) return;
     const uint32_t tile_m = tile_id / uint32_t(a.nt), tile_n = tile_id - tile_m * uint32_t(a.nt);
-    const int64_t m0 = int64_t(tile_m) * TM, n0 = int64_t(tile_n) * kTN;
+    const int64_t m0 = int64_t(tile_m) * TM, n0 = int64_t(tile_n) * TN;
     const int kp_lo = int(blockIdx.z) * a.kp_per;  // a multiple of the tile length (hence even)
     const int kp_hi = kp_lo + a.kp_per < int(L.KP) ? kp_lo + a.kp_per : int(L.KP);
 
@@ -946,9 +950,11 @@ template <int B, int XM = kXRows, bool DENSEB = false>
 muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if constexpr (B == 8 || B == 16) {
-        // (dense weight tiles: no decode to share among the rows of a tile, and two 128-row workgroups per compute
-        // unit overlap each other's prologue and epilogue)
-        const int tm = DENSEB ? 128 : int(pipe_tile_rows(L, t.M));
+        // (dense weight tiles: no decode to share among the rows of a tile, and two 4-wave workgroups per compute
+        // unit overlap each other's prologue and epilogue; 256 x 64 tiles for at most 64 output channels)
+        const bool narrow = DENSEB && L.N <= 64;
+        const int tn = narrow ? 64 : kTN;
+        const int tm = narrow ? 256 : DENSEB ? 128 : int(pipe_tile_rows(L, t.M));
         int splits = tile_splits(L, t.M, tm, true);
         if (splits > 1 && (!ws || ws_bytes < size_t(splits) * size_t(t.M) * size_t(L.N) * 4u)) splits = 1;
         const int64_t kt_per = (L.KT + splits - 1) / splits;
@@ -978,13 +984,16 @@ muw_status launch_pipe(const TileGemmArgs &t, const Layout &L, void *ws, size_t 
             a.pad = t.pad;
             a.zero_off = uint32_t(t.zero_off);
         }
-        const unsigned nt = unsigned((L.N + kTN - 1) / kTN);
+        const unsigned nt = unsigned((L.N + tn - 1) / tn);
         a.nt = int32_t(nt);
         a.n_tiles = int32_t(nt * unsigned((t.M + tm - 1) / tm));
         a.xcd_chunk = nt > 1 ? (a.n_tiles + 7) / 8 : 0;
         dim3 grid(unsigned(a.xcd_chunk ? 8 * a.xcd_chunk : a.n_tiles), 1, unsigned(splits));
         if constexpr (DENSEB) {
-            k_pipe_gemm_bf16<B, 4, XM, true><<<grid, 256, 0, st>>>(a, L);  // (always 128-row tiles)
+            if (narrow)
+                k_pipe_gemm_bf16<B, 4, XM, true, 1><<<grid, 256, 0, st>>>(a, L);
+            else
+                k_pipe_gemm_bf16<B, 4, XM, true><<<grid, 256, 0, st>>>(a, L);  // (always 4 waves)
         } else {
             if (tm == 256)
                 k_pipe_gemm_bf16<B, 8, XM, false><<<grid, 512, 0, st>>>(a, L);
