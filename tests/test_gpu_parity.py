@@ -329,6 +329,13 @@ CONV_CASES = [
     (6, 128, 14, 14, 32, 1, 1, 0, 8, "bf16"),     # the same rule for 1x1 filters: channel planes, 2-row DMA
     (3, 64, 40, 40, 32, 1, 2, 0, 16, "bf16"),     # strided 1x1: staged rows
     (2, 128, 32, 32, 56, 1, 1, 0, 16, "bf16"),    # channel planes, 8-row DMA, M = 2048
+    # 64 channels, stride 1, output as large as the input: narrow images, images much smaller than a row tile, the
+    # widest rows
+    (2, 64, 48, 48, 72, 3, 1, 1, 8, "bf16"),      # 128 x 128 macro tiles (more than 64 output channels)
+    (3, 64, 20, 12, 16, 5, 1, 2, 8, "bf16"),      # 5 x 5
+    (4, 64, 300, 1, 8, 3, 1, 1, 8, "bf16"),       # one pixel wide: every tap beside the centre column is padding
+    (40, 64, 5, 5, 16, 3, 1, 1, 16, "bf16"),      # 25-pixel images: ten of them in one 256-row tile
+    (1, 64, 56, 56, 64, 3, 1, 1, 8, "bf16"),      # 56 x 56: M = 3136 is a ragged tile count
 ]
 
 
